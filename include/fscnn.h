@@ -1,0 +1,159 @@
+/*
+ * fscnn.h -- C ABI of the MI355X (gfx950) sparse-filter / sparse-input 2-D
+ * convolution library: the hot path of FSCNN (arXiv 2212.08815).
+ *
+ * Notation (paper -> here): input T_I (C_I x H_I x W_I) -> x[N,C,H,W], dense
+ * NCHW fp32; filters T_F1..T_FN (C_F x H_F x W_F, C_F = C_I, C_O = N of the
+ * paper's Sec. 5) -> w[K,C,R,S]; stride S of Alg. 1 -> (stride_h, stride_w);
+ * output T_O -> y[N,K,Ho,Wo] with Ho = floor((H + 2*pad_h - R)/stride_h) + 1.
+ *
+ * Conventions for every entry point
+ *   - "_dev" pointers are DEVICE pointers (HIP global memory on the current
+ *     device), contiguous, 4-byte aligned, caller-owned; "_host" pointers are
+ *     ordinary host memory.  Nothing is freed or retained by the library except
+ *     the opaque handles it creates.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Every call returns a status and never throws or aborts.  All argument
+ *     checks happen before any kernel is launched.
+ *   - Handles are created and destroyed only by the library.  A handle may be
+ *     used from several streams at once for convolution calls once the plan for
+ *     the geometry exists (see fscnn_filter_prepare).
+ *   - No entry point uses a CPU fallback: without a HIP device every compute
+ *     call fails with FSCNN_ERR_DEVICE.
+ */
+#ifndef FSCNN_H
+#define FSCNN_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fscnn_filter fscnn_filter_t; /* compressed filter bank (device buffers inside)   */
+typedef struct fscnn_input fscnn_input_t;   /* compressed activation tensor (device buffers)    */
+
+typedef enum {
+    FSCNN_OK = 0,
+    FSCNN_ERR_NULL = 1,        /* a required pointer is NULL                                   */
+    FSCNN_ERR_SHAPE = 2,       /* non-positive size, negative pad, empty output, size overflow */
+    FSCNN_ERR_MISMATCH = 3,    /* x / w dimensions disagree with the handle                    */
+    FSCNN_ERR_UNSUPPORTED = 4, /* valid request outside what the kernels cover                 */
+    FSCNN_ERR_ALLOC = 5,       /* device or host allocation failed                             */
+    FSCNN_ERR_DEVICE = 6,      /* HIP runtime error (no device, launch failure, ...)           */
+    FSCNN_ERR_HANDLE = 7       /* not a live handle (bad magic word / already destroyed)       */
+} fscnn_status_t;
+
+const char *fscnn_status_string(fscnn_status_t s);
+
+/* Output extent of a convolution (host only).  Alg. 1 step 3 and Alg. 6 step 3 give
+ * (H_I - H_F)/S + 1; with the symmetric zero padding of Sec. 5 ("Other layers") this is
+ * floor((H + 2*pad - R)/stride) + 1.  FSCNN_ERR_SHAPE if any size is non-positive, a pad
+ * is negative or the filter does not fit. */
+fscnn_status_t fscnn_conv2d_out_shape(int H, int W, int R, int S, int stride_h, int stride_w,
+                                      int pad_h, int pad_w, int *Ho, int *Wo);
+
+/* ------------------------------------------------------------------ sparse filters
+ * Filter compression (Sec. 3: CSR(C) values / column indices / cumulative row counts, a
+ * sparse 4-D tensor being one sparse 3-D tensor per filter with a pointer per filter).
+ * w_dev: dense K x C x R x S fp32.  The handle holds, per output channel k, the entries
+ * with w != 0.0f (-0.0 dropped, NaN/denormals kept, values copied bit for bit) in ascending
+ * flat index (c*R + r)*S + s, i.e. sorted by input channel first.  Runs its kernels on
+ * `stream` and synchronises it once (the nonzero count sizes the buffers).
+ * K*C*R*S must be < 2^31.  *out is set only on FSCNN_OK. */
+fscnn_status_t fscnn_filter_compress(const float *w_dev, int K, int C, int R, int S,
+                                     void *stream, fscnn_filter_t **out);
+
+/* Shape and nonzero count of a handle (any output pointer may be NULL). */
+fscnn_status_t fscnn_filter_info(const fscnn_filter_t *f, int *K, int *C, int *R, int *S,
+                                 long long *nnz);
+
+/* Canonical CSR(C) view copied to HOST buffers: rowptr_host[K+1] (int32, starts with 0),
+ * idx_host[nnz] (uint32 flat (c*R+r)*S+s), val_host[nnz] (fp32).  Synchronous. */
+fscnn_status_t fscnn_filter_export(const fscnn_filter_t *f, int *rowptr_host,
+                                   unsigned *idx_host, float *val_host);
+
+/* Builds (once) the device-side plan the convolution kernel streams for this geometry:
+ * the nonzeros regrouped by (output-channel group, input-channel chunk, output channel)
+ * with each (c,r,s) packed into the byte offset of that tap inside the LDS input tile.
+ * Allocates device memory and launches on `stream` (no synchronisation).  Optional:
+ * fscnn_conv2d_sparse_filter builds the plan on first use; after that (or after this
+ * call) convolution calls with the same geometry allocate nothing.  `variant` selects a
+ * kernel configuration (0 = automatic choice; see fscnn_sf_variant_count). */
+fscnn_status_t fscnn_filter_prepare(fscnn_filter_t *f, int N, int H, int W, int stride_h,
+                                    int stride_w, int pad_h, int pad_w, int variant,
+                                    void *stream);
+
+/* Debug / test view of the plan chosen for a geometry (builds it if needed, synchronous).
+ * Writes the plan parameters into params_host[16]:
+ *   [0] variant id  [1] CC channels per chunk  [2] KG output channels per group
+ *   [3] number of chunks  [4] number of groups  [5] slot rows per channel
+ *   [6] pitch (elements per row)  [7] vector width VW  [8] records (incl. padding)
+ *   [9] 1 if the direct (untiled) kernel serves this geometry, else 0; rest 0.
+ * If segptr_host / rec_off_host / rec_val_host are non-NULL they receive
+ * segptr[groups*chunks*KG + 1], and per record the LDS byte offset and the weight.
+ * Pass NULL pointers first to learn the sizes. */
+fscnn_status_t fscnn_filter_plan_export(fscnn_filter_t *f, int N, int H, int W, int stride_h,
+                                        int stride_w, int pad_h, int pad_w, int variant,
+                                        int *params_host, int *segptr_host,
+                                        unsigned *rec_off_host, float *rec_val_host);
+
+fscnn_status_t fscnn_filter_destroy(fscnn_filter_t *f);
+
+/* Number of selectable kernel configurations of the sparse-filter convolution and a short
+ * description of each (variant ids are 1..count; 0 = automatic). */
+int fscnn_sf_variant_count(void);
+const char *fscnn_sf_variant_name(int variant);
+
+/* Sparse-filter convolution (Alg. 6: every output element, all filters; inner product of
+ * Alg. 2 over the stored nonzeros only; no kernel flip; padding as index shift):
+ *   y[n,k,oy,ox] = sum over stored (c,r,s,v) of filter k of
+ *                  v * x[n,c,oy*stride_h - pad_h + r, ox*stride_w - pad_w + s]   (0 outside)
+ *                  (+ bias_dev[k] if bias_dev != NULL) (then max(.,0) if relu != 0).
+ * x_dev: N x C x H x W, y_dev: N x K x Ho x Wo (must not alias x), bias_dev: K or NULL.
+ * fp32 accumulation in an order fixed by the plan (results are run-to-run identical).
+ * Asynchronous on `stream`.  FSCNN_ERR_MISMATCH if C differs from the handle's. */
+fscnn_status_t fscnn_conv2d_sparse_filter(fscnn_filter_t *f, const float *x_dev, int N, int C,
+                                          int H, int W, int stride_h, int stride_w, int pad_h,
+                                          int pad_w, const float *bias_dev, int relu,
+                                          float *y_dev, void *stream);
+
+/* Same, with an explicit kernel configuration (benchmarks and parity tests walk all of
+ * them).  FSCNN_ERR_UNSUPPORTED if that configuration cannot serve the geometry. */
+fscnn_status_t fscnn_conv2d_sparse_filter_v(fscnn_filter_t *f, const float *x_dev, int N,
+                                            int C, int H, int W, int stride_h, int stride_w,
+                                            int pad_h, int pad_w, const float *bias_dev,
+                                            int relu, float *y_dev, int variant, void *stream);
+
+/* ------------------------------------------------------------------ sparse inputs
+ * Activation compression (Sec. 3, sparse 3-D tensor in order O_chw: the channel run is the
+ * innermost list): one row per pixel in (n, iy, ix) raster order holding the (channel,
+ * value) pairs with x != 0.0f, channel ascending.  Synchronises `stream` once. */
+fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int W,
+                                    void *stream, fscnn_input_t **out);
+fscnn_status_t fscnn_input_info(const fscnn_input_t *in, int *N, int *C, int *H, int *W,
+                                long long *nnz);
+/* prow_host[N*H*W+1] int32, cidx_host[nnz] uint32, val_host[nnz] fp32.  Synchronous. */
+fscnn_status_t fscnn_input_export(const fscnn_input_t *in, int *prow_host, unsigned *cidx_host,
+                                  float *val_host);
+fscnn_status_t fscnn_input_destroy(fscnn_input_t *in);
+
+/* Sparse-input convolution (Sec. 4, last paragraph of "Sparse Tensor Convolution": the
+ * loops of Alg. 1 with a sparse T_I and dense filters; zero activations are skipped):
+ * same result definition as above with w_dev the dense K x C x R x S bank.  The output is
+ * written dense (N x K x Ho x Wo).  Every output element has one writer (a gather, no
+ * atomics).  Asynchronous on `stream`; allocates nothing. */
+fscnn_status_t fscnn_conv2d_sparse_input(const fscnn_input_t *in, const float *w_dev, int K,
+                                         int R, int S, int stride_h, int stride_w, int pad_h,
+                                         int pad_w, const float *bias_dev, int relu,
+                                         float *y_dev, void *stream);
+
+/* ------------------------------------------------------------------ helper
+ * Stand-alone 2x2 / stride-2 max pooling (Sec. 5 "Pooling Layers": pooling applied directly
+ * to the previous layer's output; output size floor(H/2) x floor(W/2) as in Alg. 7 step 4).
+ * Only used to chain VGG16-shaped layers; not part of the measured convolution path. */
+fscnn_status_t fscnn_maxpool2x2(const float *x_dev, int N, int C, int H, int W, float *y_dev,
+                                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FSCNN_H */

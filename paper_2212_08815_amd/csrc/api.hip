@@ -1,0 +1,504 @@
+// C-ABI entry points of libfscnn.so (declared and documented in include/fscnn.h):
+// argument validation, handle management, plan caching, kernel dispatch.  No arithmetic of
+// the method happens on the host.
+#include <limits.h>
+
+#include <new>
+
+#include "internal.h"
+
+using namespace fscnn;
+
+namespace {
+
+#define FSCNN_HIP(expr)                            \
+    do {                                           \
+        hipError_t e_ = (expr);                    \
+        if (e_ != hipSuccess) {                    \
+            (void)hipGetLastError();               \
+            return e_ == hipErrorOutOfMemory ? FSCNN_ERR_ALLOC : FSCNN_ERR_DEVICE; \
+        }                                          \
+    } while (0)
+
+fscnn_status_t out_shape(int H, int W, int R, int S, int sh, int sw, int ph, int pw, int *Ho, int *Wo)
+{
+    if (H <= 0 || W <= 0 || R <= 0 || S <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0)
+        return FSCNN_ERR_SHAPE;
+    const long long spanh = (long long)H + 2LL * ph - R;
+    const long long spanw = (long long)W + 2LL * pw - S;
+    if (spanh < 0 || spanw < 0) return FSCNN_ERR_SHAPE;
+    const long long ho = spanh / sh + 1, wo = spanw / sw + 1;
+    if (ho > INT_MAX || wo > INT_MAX) return FSCNN_ERR_SHAPE;
+    *Ho = (int)ho;
+    *Wo = (int)wo;
+    return FSCNN_OK;
+}
+
+bool fits_int(long long v) { return v > 0 && v < (1LL << 31); }
+
+fscnn_status_t have_device(int *dev)
+{
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        return FSCNN_ERR_DEVICE;
+    }
+    if (hipGetDevice(dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return FSCNN_ERR_DEVICE;
+    }
+    return FSCNN_OK;
+}
+
+bool live(const fscnn_filter_t *f) { return f && f->magic == kFilterMagic; }
+bool live(const fscnn_input_t *i) { return i && i->magic == kInputMagic; }
+
+void free_plan(SfPlan *p)
+{
+    if (!p) return;
+    if (p->segptr) (void)hipFree(p->segptr);
+    if (p->recs) (void)hipFree(p->recs);
+    delete p;
+}
+
+// Returns the plan of `variant` (>= 1) for this handle, building it on `st` when absent.
+// variant == -1 stands for the direct kernel (no device data besides the canonical CSR).
+fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan **out)
+{
+    std::lock_guard<std::mutex> lock(f->mu);
+    for (SfPlan *p : f->plans)
+        if (p->variant == variant) {
+            *out = p;
+            return FSCNN_OK;
+        }
+    SfPlan *p = new (std::nothrow) SfPlan();
+    if (!p) return FSCNN_ERR_ALLOC;
+    p->variant = variant;
+    if (variant == -1) {
+        p->direct = true;
+        f->plans.push_back(p);
+        *out = p;
+        return FSCNN_OK;
+    }
+    if (!sf_variant_geom(variant, f->R, f->S, &p->g)) {
+        delete p;
+        return FSCNN_ERR_UNSUPPORTED;
+    }
+    const SfGeom &g = p->g;
+    p->NCH = (f->C + g.CC - 1) / g.CC;
+    p->NG = (f->K + g.KG - 1) / g.KG;
+    const long long nb = (long long)p->NG * p->NCH * g.KG;
+    const long long cap = f->nnz + nb * (g.pad_to - 1);
+    if (!fits_int(nb + 1) || cap >= (1LL << 31)) {
+        delete p;
+        return FSCNN_ERR_UNSUPPORTED;
+    }
+    int *cnt = nullptr;
+    hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)nb);
+    if (e == hipSuccess) e = hipMalloc(&p->segptr, sizeof(int) * (size_t)(nb + 1));
+    if (e == hipSuccess) e = hipMalloc(&p->recs, sizeof(Rec) * (size_t)(cap > 0 ? cap : 1));
+    if (e == hipSuccess)
+        e = launch_plan_count(f->rowptr, f->idx, f->K, f->R * f->S, g.CC, g.KG, p->NCH, p->NG,
+                              g.pad_to, cnt, st);
+    if (e == hipSuccess) e = launch_exclusive_scan(cnt, p->segptr, nb, st);
+    if (e == hipSuccess)
+        e = launch_plan_fill(f->rowptr, f->idx, f->val, f->K, f->R, f->S, g, p->NCH, p->NG,
+                             p->segptr, p->recs, st);
+    // The plan may be used from other streams and `cnt` is released here: wait for the build.
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (cnt) (void)hipFree(cnt);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        free_plan(p);
+        return e == hipErrorOutOfMemory ? FSCNN_ERR_ALLOC : FSCNN_ERR_DEVICE;
+    }
+    p->nrec = cap;
+    f->plans.push_back(p);
+    *out = p;
+    return FSCNN_OK;
+}
+
+// Which variant serves this geometry: `variant` > 0 is taken as is (checked), 0 = automatic,
+// anything the tiled kernel cannot do goes to the direct kernel (-1).
+fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int sh, int sw,
+                               int variant, int *resolved)
+{
+    const bool tiled_ok = (sh == 1 && sw == 1);
+    if (variant < 0 || variant > sf_variant_count()) return FSCNN_ERR_UNSUPPORTED;
+    if (variant > 0) {
+        SfGeom g;
+        if (!tiled_ok || !sf_variant_geom(variant, f->R, f->S, &g)) return FSCNN_ERR_UNSUPPORTED;
+        *resolved = variant;
+        return FSCNN_OK;
+    }
+    int v = tiled_ok ? sf_choose_variant(N, f->C, f->K, H, W, f->R, f->S) : 0;
+    *resolved = v > 0 ? v : -1;
+    return FSCNN_OK;
+}
+
+fscnn_status_t check_conv_args(const fscnn_filter_t *f, const float *x, int N, int C, int H, int W,
+                               int sh, int sw, int ph, int pw, const float *y, int *Ho, int *Wo)
+{
+    if (!f || !x || !y) return FSCNN_ERR_NULL;
+    if (!live(f)) return FSCNN_ERR_HANDLE;
+    if (N <= 0 || C <= 0) return FSCNN_ERR_SHAPE;
+    fscnn_status_t s = out_shape(H, W, f->R, f->S, sh, sw, ph, pw, Ho, Wo);
+    if (s != FSCNN_OK) return s;
+    if (C != f->C) return FSCNN_ERR_MISMATCH;
+    if (!fits_int((long long)N * C * H * W) || !fits_int((long long)N * f->K * *Ho * *Wo))
+        return FSCNN_ERR_UNSUPPORTED;
+    if (x == y) return FSCNN_ERR_UNSUPPORTED;
+    return FSCNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *fscnn_status_string(fscnn_status_t s)
+{
+    switch (s) {
+        case FSCNN_OK: return "ok";
+        case FSCNN_ERR_NULL: return "null pointer argument";
+        case FSCNN_ERR_SHAPE: return "invalid shape (non-positive size, negative pad or empty output)";
+        case FSCNN_ERR_MISMATCH: return "tensor dimensions do not match the handle";
+        case FSCNN_ERR_UNSUPPORTED: return "request outside what the kernels cover";
+        case FSCNN_ERR_ALLOC: return "allocation failed";
+        case FSCNN_ERR_DEVICE: return "HIP runtime error or no device";
+        case FSCNN_ERR_HANDLE: return "not a live handle";
+    }
+    return "unknown status";
+}
+
+fscnn_status_t fscnn_conv2d_out_shape(int H, int W, int R, int S, int sh, int sw, int ph, int pw,
+                                      int *Ho, int *Wo)
+{
+    if (!Ho || !Wo) return FSCNN_ERR_NULL;
+    return out_shape(H, W, R, S, sh, sw, ph, pw, Ho, Wo);
+}
+
+fscnn_status_t fscnn_filter_compress(const float *w_dev, int K, int C, int R, int S, void *stream,
+                                     fscnn_filter_t **out)
+{
+    if (!w_dev || !out) return FSCNN_ERR_NULL;
+    if (K <= 0 || C <= 0 || R <= 0 || S <= 0) return FSCNN_ERR_SHAPE;
+    const long long row = (long long)C * R * S;
+    if (!fits_int(row) || !fits_int(row * K)) return FSCNN_ERR_SHAPE;
+    int dev;
+    fscnn_status_t s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+
+    fscnn_filter_t *f = new (std::nothrow) fscnn_filter();
+    if (!f) return FSCNN_ERR_ALLOC;
+    f->magic = kFilterMagic;
+    f->device = dev;
+    f->K = K; f->C = C; f->R = R; f->S = S;
+    f->nnz = 0;
+    f->rowptr = nullptr; f->idx = nullptr; f->val = nullptr;
+    int *cnt = nullptr;
+    int total = 0;
+    hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)K);
+    if (e == hipSuccess) e = hipMalloc(&f->rowptr, sizeof(int) * (size_t)(K + 1));
+    if (e == hipSuccess) e = launch_filter_count(w_dev, K, row, cnt, st);
+    if (e == hipSuccess) e = launch_exclusive_scan(cnt, f->rowptr, K, st);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(&total, f->rowptr + K, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e == hipSuccess) {
+        f->nnz = total;
+        const size_t n = total > 0 ? (size_t)total : 1;
+        e = hipMalloc(&f->idx, sizeof(uint32_t) * n);
+        if (e == hipSuccess) e = hipMalloc(&f->val, sizeof(float) * n);
+    }
+    if (e == hipSuccess) e = launch_filter_pack(w_dev, K, row, f->rowptr, f->idx, f->val, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (cnt) (void)hipFree(cnt);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        if (f->rowptr) (void)hipFree(f->rowptr);
+        if (f->idx) (void)hipFree(f->idx);
+        if (f->val) (void)hipFree(f->val);
+        f->magic = 0;
+        delete f;
+        return e == hipErrorOutOfMemory ? FSCNN_ERR_ALLOC : FSCNN_ERR_DEVICE;
+    }
+    *out = f;
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_filter_info(const fscnn_filter_t *f, int *K, int *C, int *R, int *S,
+                                 long long *nnz)
+{
+    if (!f) return FSCNN_ERR_NULL;
+    if (!live(f)) return FSCNN_ERR_HANDLE;
+    if (K) *K = f->K;
+    if (C) *C = f->C;
+    if (R) *R = f->R;
+    if (S) *S = f->S;
+    if (nnz) *nnz = f->nnz;
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_filter_export(const fscnn_filter_t *f, int *rowptr_host, unsigned *idx_host,
+                                   float *val_host)
+{
+    if (!f || !rowptr_host) return FSCNN_ERR_NULL;
+    if (!live(f)) return FSCNN_ERR_HANDLE;
+    if (f->nnz > 0 && (!idx_host || !val_host)) return FSCNN_ERR_NULL;
+    FSCNN_HIP(hipMemcpy(rowptr_host, f->rowptr, sizeof(int) * (size_t)(f->K + 1), hipMemcpyDeviceToHost));
+    if (f->nnz > 0) {
+        FSCNN_HIP(hipMemcpy(idx_host, f->idx, sizeof(uint32_t) * (size_t)f->nnz, hipMemcpyDeviceToHost));
+        FSCNN_HIP(hipMemcpy(val_host, f->val, sizeof(float) * (size_t)f->nnz, hipMemcpyDeviceToHost));
+    }
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_filter_prepare(fscnn_filter_t *f, int N, int H, int W, int sh, int sw, int ph,
+                                    int pw, int variant, void *stream)
+{
+    if (!f) return FSCNN_ERR_NULL;
+    if (!live(f)) return FSCNN_ERR_HANDLE;
+    if (N <= 0) return FSCNN_ERR_SHAPE;
+    int Ho, Wo;
+    fscnn_status_t s = out_shape(H, W, f->R, f->S, sh, sw, ph, pw, &Ho, &Wo);
+    if (s != FSCNN_OK) return s;
+    int v;
+    s = resolve_variant(f, N, H, W, sh, sw, variant, &v);
+    if (s != FSCNN_OK) return s;
+    SfPlan *p;
+    return get_plan(f, v, (hipStream_t)stream, &p);
+}
+
+fscnn_status_t fscnn_filter_plan_export(fscnn_filter_t *f, int N, int H, int W, int sh, int sw,
+                                        int ph, int pw, int variant, int *params_host,
+                                        int *segptr_host, unsigned *rec_off_host,
+                                        float *rec_val_host)
+{
+    if (!f || !params_host) return FSCNN_ERR_NULL;
+    if (!live(f)) return FSCNN_ERR_HANDLE;
+    if (N <= 0) return FSCNN_ERR_SHAPE;
+    int Ho, Wo;
+    fscnn_status_t s = out_shape(H, W, f->R, f->S, sh, sw, ph, pw, &Ho, &Wo);
+    if (s != FSCNN_OK) return s;
+    int v;
+    s = resolve_variant(f, N, H, W, sh, sw, variant, &v);
+    if (s != FSCNN_OK) return s;
+    SfPlan *p;
+    s = get_plan(f, v, nullptr, &p);
+    if (s != FSCNN_OK) return s;
+    for (int i = 0; i < 16; ++i) params_host[i] = 0;
+    params_host[0] = p->variant;
+    params_host[9] = p->direct ? 1 : 0;
+    if (p->direct) return FSCNN_OK;
+    params_host[1] = p->g.CC;
+    params_host[2] = p->g.KG;
+    params_host[3] = p->NCH;
+    params_host[4] = p->NG;
+    params_host[5] = p->g.NSLOT;
+    params_host[6] = p->g.PITCH;
+    params_host[7] = p->g.VW;
+    params_host[8] = (int)p->nrec;
+    const long long nb = (long long)p->NG * p->NCH * p->g.KG;
+    if (segptr_host)
+        FSCNN_HIP(hipMemcpy(segptr_host, p->segptr, sizeof(int) * (size_t)(nb + 1), hipMemcpyDeviceToHost));
+    if ((rec_off_host || rec_val_host) && p->nrec > 0) {
+        if (!rec_off_host || !rec_val_host) return FSCNN_ERR_NULL;
+        Rec *tmp = new (std::nothrow) Rec[(size_t)p->nrec];
+        if (!tmp) return FSCNN_ERR_ALLOC;
+        hipError_t e = hipMemcpy(tmp, p->recs, sizeof(Rec) * (size_t)p->nrec, hipMemcpyDeviceToHost);
+        if (e == hipSuccess)
+            for (long long i = 0; i < p->nrec; ++i) {
+                rec_off_host[i] = tmp[i].off;
+                rec_val_host[i] = tmp[i].val;
+            }
+        delete[] tmp;
+        FSCNN_HIP(e);
+    }
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_filter_destroy(fscnn_filter_t *f)
+{
+    if (!f) return FSCNN_ERR_NULL;
+    if (!live(f)) return FSCNN_ERR_HANDLE;
+    f->magic = 0;
+    for (SfPlan *p : f->plans) free_plan(p);
+    f->plans.clear();
+    if (f->rowptr) (void)hipFree(f->rowptr);
+    if (f->idx) (void)hipFree(f->idx);
+    if (f->val) (void)hipFree(f->val);
+    delete f;
+    return FSCNN_OK;
+}
+
+int fscnn_sf_variant_count(void) { return sf_variant_count(); }
+const char *fscnn_sf_variant_name(int variant) { return sf_variant_name(variant); }
+
+fscnn_status_t fscnn_conv2d_sparse_filter_v(fscnn_filter_t *f, const float *x_dev, int N, int C,
+                                            int H, int W, int sh, int sw, int ph, int pw,
+                                            const float *bias_dev, int relu, float *y_dev,
+                                            int variant, void *stream)
+{
+    int Ho, Wo;
+    fscnn_status_t s = check_conv_args(f, x_dev, N, C, H, W, sh, sw, ph, pw, y_dev, &Ho, &Wo);
+    if (s != FSCNN_OK) return s;
+    int v;
+    s = resolve_variant(f, N, H, W, sh, sw, variant, &v);
+    if (s != FSCNN_OK) return s;
+    int dev;
+    s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    SfPlan *p;
+    s = get_plan(f, v, st, &p);
+    if (s != FSCNN_OK) return s;
+    if (p->direct) {
+        FSCNN_HIP(launch_conv_sf_direct(f->rowptr, f->idx, f->val, x_dev, N, C, H, W, f->K, f->R,
+                                        f->S, Ho, Wo, sh, sw, ph, pw, bias_dev, relu, y_dev, st));
+    } else {
+        FSCNN_HIP(launch_conv_sf_tiled(*p, x_dev, N, C, H, W, f->K, Ho, Wo, ph, pw, bias_dev, relu,
+                                       y_dev, st));
+    }
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_conv2d_sparse_filter(fscnn_filter_t *f, const float *x_dev, int N, int C, int H,
+                                          int W, int sh, int sw, int ph, int pw,
+                                          const float *bias_dev, int relu, float *y_dev,
+                                          void *stream)
+{
+    return fscnn_conv2d_sparse_filter_v(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, relu, y_dev,
+                                        0, stream);
+}
+
+fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int W, void *stream,
+                                    fscnn_input_t **out)
+{
+    if (!x_dev || !out) return FSCNN_ERR_NULL;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return FSCNN_ERR_SHAPE;
+    const long long npix = (long long)N * H * W;
+    if (!fits_int(npix + 1) || !fits_int(npix * C)) return FSCNN_ERR_SHAPE;
+    const int CC = kSiCC, NCH = (C + CC - 1) / CC;
+    if (!fits_int(npix * (NCH + 1))) return FSCNN_ERR_UNSUPPORTED;
+    int dev;
+    fscnn_status_t s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+
+    fscnn_input_t *in = new (std::nothrow) fscnn_input();
+    if (!in) return FSCNN_ERR_ALLOC;
+    in->magic = kInputMagic;
+    in->device = dev;
+    in->N = N; in->C = C; in->H = H; in->W = W;
+    in->nnz = 0; in->CC = CC; in->NCH = NCH;
+    in->prow = nullptr; in->cidx = nullptr; in->xval = nullptr; in->cptr = nullptr;
+    int *cnt = nullptr;
+    int total = 0;
+    hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)npix);
+    if (e == hipSuccess) e = hipMalloc(&in->prow, sizeof(int) * (size_t)(npix + 1));
+    if (e == hipSuccess) e = hipMalloc(&in->cptr, sizeof(int) * (size_t)(npix * (NCH + 1)));
+    if (e == hipSuccess) e = launch_input_count(x_dev, N, C, H, W, cnt, st);
+    if (e == hipSuccess) e = launch_exclusive_scan(cnt, in->prow, npix, st);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(&total, in->prow + npix, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e == hipSuccess) {
+        in->nnz = total;
+        const size_t n = total > 0 ? (size_t)total : 1;
+        e = hipMalloc(&in->cidx, sizeof(uint32_t) * n);
+        if (e == hipSuccess) e = hipMalloc(&in->xval, sizeof(float) * n);
+    }
+    if (e == hipSuccess)
+        e = launch_input_fill(x_dev, N, C, H, W, in->prow, CC, NCH, in->cidx, in->xval, in->cptr, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (cnt) (void)hipFree(cnt);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        if (in->prow) (void)hipFree(in->prow);
+        if (in->cptr) (void)hipFree(in->cptr);
+        if (in->cidx) (void)hipFree(in->cidx);
+        if (in->xval) (void)hipFree(in->xval);
+        in->magic = 0;
+        delete in;
+        return e == hipErrorOutOfMemory ? FSCNN_ERR_ALLOC : FSCNN_ERR_DEVICE;
+    }
+    *out = in;
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_input_info(const fscnn_input_t *in, int *N, int *C, int *H, int *W,
+                                long long *nnz)
+{
+    if (!in) return FSCNN_ERR_NULL;
+    if (!live(in)) return FSCNN_ERR_HANDLE;
+    if (N) *N = in->N;
+    if (C) *C = in->C;
+    if (H) *H = in->H;
+    if (W) *W = in->W;
+    if (nnz) *nnz = in->nnz;
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_input_export(const fscnn_input_t *in, int *prow_host, unsigned *cidx_host,
+                                  float *val_host)
+{
+    if (!in || !prow_host) return FSCNN_ERR_NULL;
+    if (!live(in)) return FSCNN_ERR_HANDLE;
+    if (in->nnz > 0 && (!cidx_host || !val_host)) return FSCNN_ERR_NULL;
+    const size_t npix = (size_t)in->N * in->H * in->W;
+    FSCNN_HIP(hipMemcpy(prow_host, in->prow, sizeof(int) * (npix + 1), hipMemcpyDeviceToHost));
+    if (in->nnz > 0) {
+        FSCNN_HIP(hipMemcpy(cidx_host, in->cidx, sizeof(uint32_t) * (size_t)in->nnz, hipMemcpyDeviceToHost));
+        FSCNN_HIP(hipMemcpy(val_host, in->xval, sizeof(float) * (size_t)in->nnz, hipMemcpyDeviceToHost));
+    }
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_input_destroy(fscnn_input_t *in)
+{
+    if (!in) return FSCNN_ERR_NULL;
+    if (!live(in)) return FSCNN_ERR_HANDLE;
+    in->magic = 0;
+    if (in->prow) (void)hipFree(in->prow);
+    if (in->cptr) (void)hipFree(in->cptr);
+    if (in->cidx) (void)hipFree(in->cidx);
+    if (in->xval) (void)hipFree(in->xval);
+    delete in;
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_conv2d_sparse_input(const fscnn_input_t *in, const float *w_dev, int K, int R,
+                                         int S, int sh, int sw, int ph, int pw,
+                                         const float *bias_dev, int relu, float *y_dev, void *stream)
+{
+    if (!in || !w_dev || !y_dev) return FSCNN_ERR_NULL;
+    if (!live(in)) return FSCNN_ERR_HANDLE;
+    if (K <= 0) return FSCNN_ERR_SHAPE;
+    int Ho, Wo;
+    fscnn_status_t s = out_shape(in->H, in->W, R, S, sh, sw, ph, pw, &Ho, &Wo);
+    if (s != FSCNN_OK) return s;
+    if (!fits_int((long long)K * in->C * R * S) || !fits_int((long long)in->N * K * Ho * Wo))
+        return FSCNN_ERR_UNSUPPORTED;
+    int dev;
+    s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    FSCNN_HIP(launch_conv_si(in, w_dev, K, R, S, Ho, Wo, sh, sw, ph, pw, bias_dev, relu, y_dev,
+                             (hipStream_t)stream));
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_maxpool2x2(const float *x_dev, int N, int C, int H, int W, float *y_dev,
+                                void *stream)
+{
+    if (!x_dev || !y_dev) return FSCNN_ERR_NULL;
+    if (N <= 0 || C <= 0 || H < 2 || W < 2) return FSCNN_ERR_SHAPE;
+    if (!fits_int((long long)N * C * H * W)) return FSCNN_ERR_UNSUPPORTED;
+    int dev;
+    fscnn_status_t s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    FSCNN_HIP(launch_maxpool2x2(x_dev, N, C, H, W, y_dev, (hipStream_t)stream));
+    return FSCNN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,316 @@
+// Compression kernels: dense filter bank -> CSR(C) (count, scan, ordered pack), the
+// regrouping of the nonzeros into the (group, chunk, channel) stream the convolution
+// kernel reads, dense activation -> per-pixel channel lists, and the helper max-pool.
+//
+// The paper (Sec. 3) fixes the format only: values, column indices and cumulative row
+// counts that start with 0, one row per filter.  The construction used here is
+// count -> exclusive scan -> order-preserving compaction, which makes the result unique
+// (ascending flat index inside each row) and independent of thread scheduling.
+#include "internal.h"
+
+namespace fscnn {
+
+namespace {
+
+constexpr int kBlock = 256;
+
+__device__ inline int lane_id() { return threadIdx.x & 63; }
+
+// Exclusive prefix of `flag` over the work-group in thread order, plus the group total.
+// Uses one ballot per wave and a small LDS array for the wave totals.
+__device__ inline int block_exclusive_count(bool flag, int *wave_tot /* LDS, >= blockDim/64 */,
+                                            int *total)
+{
+    const unsigned long long m = __ballot(flag);
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int nw = blockDim.x >> 6;
+    const int within = __popcll(m & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_tot[wave] = __popcll(m);
+    __syncthreads();
+    int before = 0, tot = 0;
+    for (int i = 0; i < nw; ++i) {
+        const int t = wave_tot[i];
+        if (i < wave) before += t;
+        tot += t;
+    }
+    __syncthreads();  // wave_tot may be reused by the caller's next round
+    *total = tot;
+    return before + within;
+}
+
+// ---- A1: per output channel, the number of entries with w != 0 ------------------------
+__global__ void __launch_bounds__(kBlock) filter_count_kernel(const float *__restrict__ w,
+                                                              long long row, int *__restrict__ cnt)
+{
+    __shared__ int part[kBlock / 64];
+    const float *wk = w + (long long)blockIdx.x * row;
+    int c = 0;
+    for (long long f = threadIdx.x; f < row; f += kBlock) c += (wk[f] != 0.0f) ? 1 : 0;
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o, 64);
+    if (lane_id() == 0) part[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+        for (int i = 0; i < kBlock / 64; ++i) t += part[i];
+        cnt[blockIdx.x] = t;
+    }
+}
+
+// ---- exclusive scan of n ints into out[0..n] (out[n] = total); one work-group ---------
+constexpr int kScanThreads = 1024;
+__global__ void __launch_bounds__(kScanThreads) exclusive_scan_kernel(const int *__restrict__ in,
+                                                                      int *__restrict__ out,
+                                                                      long long n)
+{
+    __shared__ int sums[kScanThreads];
+    const long long per = (n + kScanThreads - 1) / kScanThreads;
+    const long long lo = (long long)threadIdx.x * per;
+    const long long hi = lo + per < n ? lo + per : n;
+    int s = 0;
+    for (long long i = lo; i < hi; ++i) s += in[i];
+    sums[threadIdx.x] = s;
+    __syncthreads();
+    // Hillis-Steele inclusive scan over the 1024 partial sums
+    for (int o = 1; o < kScanThreads; o <<= 1) {
+        int v = (int)threadIdx.x >= o ? sums[threadIdx.x - o] : 0;
+        __syncthreads();
+        sums[threadIdx.x] += v;
+        __syncthreads();
+    }
+    int run = threadIdx.x == 0 ? 0 : sums[threadIdx.x - 1];
+    for (long long i = lo; i < hi; ++i) {
+        const int v = in[i];
+        out[i] = run;
+        run += v;
+    }
+    if (threadIdx.x == kScanThreads - 1) out[n] = sums[kScanThreads - 1];
+}
+
+// ---- A2: ordered pack of row k into idx/val at rowptr[k] ------------------------------
+__global__ void __launch_bounds__(kBlock) filter_pack_kernel(const float *__restrict__ w,
+                                                             long long row,
+                                                             const int *__restrict__ rowptr,
+                                                             uint32_t *__restrict__ idx,
+                                                             float *__restrict__ val)
+{
+    __shared__ int wave_tot[kBlock / 64];
+    const int k = blockIdx.x;
+    const float *wk = w + (long long)k * row;
+    long long base = rowptr[k];
+    for (long long f0 = 0; f0 < row; f0 += kBlock) {
+        const long long f = f0 + threadIdx.x;
+        float v = 0.0f;
+        if (f < row) v = wk[f];
+        const bool nz = (f < row) && (v != 0.0f);
+        int tot;
+        const int pos = block_exclusive_count(nz, wave_tot, &tot);
+        if (nz) {
+            idx[base + pos] = (uint32_t)f;
+            val[base + pos] = v;
+        }
+        base += tot;
+    }
+}
+
+// ---- A3: regroup into (group g, chunk ci, channel-in-group kk) buckets -----------------
+// Rows are ascending in the flat index, hence ascending in c: the entries of chunk ci are the
+// contiguous run with ci*CC*R*S <= flat < (ci+1)*CC*R*S, found by binary search.
+__device__ inline int lower_bound_u32(const uint32_t *a, int lo, int hi, uint32_t key)
+{
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void plan_count_kernel(const int *__restrict__ rowptr, const uint32_t *__restrict__ idx,
+                                  int K, int RS, int CC, int KG, int NCH, int NG, int pad_to,
+                                  int *__restrict__ cnt)
+{
+    const long long b = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long nb = (long long)NG * NCH * KG;
+    if (b >= nb) return;
+    const int kk = (int)(b % KG);
+    const int ci = (int)((b / KG) % NCH);
+    const int g = (int)(b / ((long long)KG * NCH));
+    const int k = g * KG + kk;
+    int c = 0;
+    if (k < K) {
+        const int lo = rowptr[k], hi = rowptr[k + 1];
+        const int a = lower_bound_u32(idx, lo, hi, (uint32_t)ci * CC * RS);
+        const int e = lower_bound_u32(idx, lo, hi, (uint32_t)(ci + 1) * CC * RS);
+        c = e - a;
+        c = (c + pad_to - 1) / pad_to * pad_to;
+    }
+    cnt[b] = c;
+}
+
+__global__ void plan_fill_kernel(const int *__restrict__ rowptr, const uint32_t *__restrict__ idx,
+                                 const float *__restrict__ val, int K, int R, int S, int CC,
+                                 int KG, int NCH, int NG, int NSLOT, int PITCH, int VW,
+                                 const int *__restrict__ segptr, Rec *__restrict__ recs)
+{
+    const long long b = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long nb = (long long)NG * NCH * KG;
+    if (b >= nb) return;
+    const int kk = (int)(b % KG);
+    const int ci = (int)((b / KG) % NCH);
+    const int g = (int)(b / ((long long)KG * NCH));
+    const int k = g * KG + kk;
+    if (k >= K) return;
+    const int RS = R * S;
+    const int lo = rowptr[k], hi = rowptr[k + 1];
+    const int a = lower_bound_u32(idx, lo, hi, (uint32_t)ci * CC * RS);
+    const int e = lower_bound_u32(idx, lo, hi, (uint32_t)(ci + 1) * CC * RS);
+    int o = segptr[b];
+    const int oend = segptr[b + 1];
+    for (int i = a; i < e; ++i, ++o) {
+        const uint32_t f = idx[i];
+        const int c = (int)(f / RS) - ci * CC;
+        const int rs = (int)(f % RS);
+        const int r = rs / S, s = rs % S;
+        Rec rec;
+        rec.off = (uint32_t)(((c * NSLOT + r) * PITCH + s) * VW * 4);
+        rec.val = val[i];
+        recs[o] = rec;
+    }
+    for (; o < oend; ++o) {  // padding records (weight +0.0 at the tile origin)
+        Rec rec;
+        rec.off = 0u;
+        rec.val = 0.0f;
+        recs[o] = rec;
+    }
+}
+
+// ---- A7: compressed activation, rows = pixels, columns = channels ----------------------
+__global__ void __launch_bounds__(kBlock) input_count_kernel(const float *__restrict__ x, int N,
+                                                             int C, long long HW,
+                                                             int *__restrict__ cnt)
+{
+    const long long p = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (p >= (long long)N * HW) return;
+    const long long n = p / HW, q = p % HW;
+    const float *xp = x + n * C * HW + q;
+    int c = 0;
+    for (int ch = 0; ch < C; ++ch) c += (xp[(long long)ch * HW] != 0.0f) ? 1 : 0;
+    cnt[p] = c;
+}
+
+__global__ void __launch_bounds__(kBlock) input_fill_kernel(const float *__restrict__ x, int N,
+                                                            int C, long long HW,
+                                                            const int *__restrict__ prow, int CC,
+                                                            int NCH, uint32_t *__restrict__ cidx,
+                                                            float *__restrict__ xval,
+                                                            int *__restrict__ cptr)
+{
+    const long long p = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (p >= (long long)N * HW) return;
+    const long long n = p / HW, q = p % HW;
+    const float *xp = x + n * C * HW + q;
+    int o = prow[p];
+    int *cp = cptr + p * (NCH + 1);
+    for (int j = 0; j < NCH; ++j) {
+        cp[j] = o;
+        const int c1 = (j + 1) * CC < C ? (j + 1) * CC : C;
+        for (int ch = j * CC; ch < c1; ++ch) {
+            const float v = xp[(long long)ch * HW];
+            if (v != 0.0f) {
+                cidx[o] = (uint32_t)ch;
+                xval[o] = v;
+                ++o;
+            }
+        }
+    }
+    cp[NCH] = o;
+}
+
+// ---- helper: 2x2 / stride-2 max pooling ------------------------------------------------
+__global__ void __launch_bounds__(kBlock) maxpool2x2_kernel(const float *__restrict__ x,
+                                                            long long NC, int H, int W, int Ho,
+                                                            int Wo, float *__restrict__ y)
+{
+    const long long o = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (o >= NC * Ho * Wo) return;
+    const int ox = (int)(o % Wo);
+    const int oy = (int)((o / Wo) % Ho);
+    const long long nc = o / ((long long)Wo * Ho);
+    const float *p = x + (nc * H + 2 * oy) * W + 2 * ox;
+    float m = p[0];
+    m = p[1] > m ? p[1] : m;
+    m = p[W] > m ? p[W] : m;
+    m = p[W + 1] > m ? p[W + 1] : m;
+    y[o] = m;
+}
+
+inline unsigned blocks_for(long long n, int per) { return (unsigned)((n + per - 1) / per); }
+
+}  // namespace
+
+hipError_t launch_filter_count(const float *w, int K, long long row, int *cnt, hipStream_t st)
+{
+    hipLaunchKernelGGL(filter_count_kernel, dim3(K), dim3(kBlock), 0, st, w, row, cnt);
+    return hipGetLastError();
+}
+
+hipError_t launch_exclusive_scan(const int *in, int *out, long long n, hipStream_t st)
+{
+    hipLaunchKernelGGL(exclusive_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, in, out, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_filter_pack(const float *w, int K, long long row, const int *rowptr,
+                              uint32_t *idx, float *val, hipStream_t st)
+{
+    hipLaunchKernelGGL(filter_pack_kernel, dim3(K), dim3(kBlock), 0, st, w, row, rowptr, idx, val);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan_count(const int *rowptr, const uint32_t *idx, int K, int RS, int CC, int KG,
+                             int NCH, int NG, int pad_to, int *cnt, hipStream_t st)
+{
+    const long long nb = (long long)NG * NCH * KG;
+    hipLaunchKernelGGL(plan_count_kernel, dim3(blocks_for(nb, kBlock)), dim3(kBlock), 0, st, rowptr,
+                       idx, K, RS, CC, KG, NCH, NG, pad_to, cnt);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float *val, int K, int R,
+                            int S, const SfGeom &g, int NCH, int NG, const int *segptr, Rec *recs,
+                            hipStream_t st)
+{
+    const long long nb = (long long)NG * NCH * g.KG;
+    hipLaunchKernelGGL(plan_fill_kernel, dim3(blocks_for(nb, kBlock)), dim3(kBlock), 0, st, rowptr,
+                       idx, val, K, R, S, g.CC, g.KG, NCH, NG, g.NSLOT, g.PITCH, g.VW, segptr, recs);
+    return hipGetLastError();
+}
+
+hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int *cnt, hipStream_t st)
+{
+    const long long HW = (long long)H * W;
+    hipLaunchKernelGGL(input_count_kernel, dim3(blocks_for(N * HW, kBlock)), dim3(kBlock), 0, st, x,
+                       N, C, HW, cnt);
+    return hipGetLastError();
+}
+
+hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, const int *prow, int CC,
+                             int NCH, uint32_t *cidx, float *xval, int *cptr, hipStream_t st)
+{
+    const long long HW = (long long)H * W;
+    hipLaunchKernelGGL(input_fill_kernel, dim3(blocks_for(N * HW, kBlock)), dim3(kBlock), 0, st, x,
+                       N, C, HW, prow, CC, NCH, cidx, xval, cptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool2x2(const float *x, int N, int C, int H, int W, float *y, hipStream_t st)
+{
+    const int Ho = H / 2, Wo = W / 2;
+    const long long n = (long long)N * C * Ho * Wo;
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(maxpool2x2_kernel, dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, st, x,
+                       (long long)N * C, H, W, Ho, Wo, y);
+    return hipGetLastError();
+}
+
+}  // namespace fscnn

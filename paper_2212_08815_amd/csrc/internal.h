@@ -1,0 +1,113 @@
+// Internal declarations shared by the translation units of libfscnn.so.
+// Nothing here is part of the C ABI (see include/fscnn.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <mutex>
+#include <vector>
+
+#include "fscnn.h"
+
+namespace fscnn {
+
+constexpr uint64_t kFilterMagic = 0x4653434e4e464c54ull;  // "FSCNNFLT"
+constexpr uint64_t kInputMagic = 0x4653434e4e494e50ull;   // "FSCNNINP"
+
+// One nonzero as the convolution kernel streams it: the byte offset of the tap
+// (c mod CC, r, s) inside the LDS input tile, and the weight (the paper's node
+// {index, value}, Sec. 3, with the index pre-multiplied for the tile geometry).
+struct Rec {
+    uint32_t off;
+    float val;
+};
+
+// Geometry of one kernel configuration of the tiled sparse-filter convolution.
+struct SfGeom {
+    int LW, VW, NV, SLOTS, WAVES, CC;  // template parameters
+    int R, S;                          // filter extent the instance is built for
+    int TH, TW;                        // output tile
+    int NSLOT, PITCH;                  // LDS rows (vector slots) per channel, elements per row
+    int KG;                            // output channels per work-group
+    int lds_bytes;
+    int pad_to;                        // records per segment are padded to a multiple of this
+};
+
+struct SfPlan {
+    int variant = 0;   // 1-based index into the variant table
+    bool direct = false;
+    SfGeom g{};
+    int NCH = 0, NG = 0;
+    long long nrec = 0;       // records written (including padding records)
+    int *segptr = nullptr;    // [NG*NCH*KG + 1]
+    Rec *recs = nullptr;      // [nrec]
+};
+
+struct SiGeom {
+    int CC;  // channels per chunk of the compressed activation's chunk pointers
+};
+
+}  // namespace fscnn
+
+struct fscnn_filter {
+    uint64_t magic;
+    int device;
+    int K, C, R, S;
+    long long nnz;
+    int *rowptr;    // device [K+1]
+    uint32_t *idx;  // device [nnz]
+    float *val;     // device [nnz]
+    std::mutex mu;
+    std::vector<fscnn::SfPlan *> plans;
+};
+
+struct fscnn_input {
+    uint64_t magic;
+    int device;
+    int N, C, H, W;
+    long long nnz;
+    int CC, NCH;     // chunking of the channel axis used by cptr
+    int *prow;       // device [N*H*W + 1]
+    uint32_t *cidx;  // device [nnz]
+    float *xval;     // device [nnz]
+    int *cptr;       // device [N*H*W*(NCH+1)]: first entry of pixel p with c >= j*CC
+};
+
+namespace fscnn {
+
+// ---- compress.hip
+hipError_t launch_filter_count(const float *w, int K, long long row, int *cnt, hipStream_t st);
+hipError_t launch_exclusive_scan(const int *in, int *out, long long n, hipStream_t st);
+hipError_t launch_filter_pack(const float *w, int K, long long row, const int *rowptr,
+                              uint32_t *idx, float *val, hipStream_t st);
+hipError_t launch_plan_count(const int *rowptr, const uint32_t *idx, int K, int RS, int CC, int KG,
+                             int NCH, int NG, int pad_to, int *cnt, hipStream_t st);
+hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float *val, int K, int R,
+                            int S, const SfGeom &g, int NCH, int NG, const int *segptr, Rec *recs,
+                            hipStream_t st);
+hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int *cnt, hipStream_t st);
+hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, const int *prow, int CC,
+                             int NCH, uint32_t *cidx, float *xval, int *cptr, hipStream_t st);
+hipError_t launch_maxpool2x2(const float *x, int N, int C, int H, int W, float *y, hipStream_t st);
+
+// ---- conv_sf.hip
+int sf_variant_count();
+const char *sf_variant_name(int variant);
+bool sf_variant_geom(int variant, int R, int S, SfGeom *g);  // false if the variant cannot serve RxS
+int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S);
+hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
+                                int Ho, int Wo, int ph, int pw, const float *bias, int relu,
+                                float *y, hipStream_t st);
+hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const float *val,
+                                 const float *x, int N, int C, int H, int W, int K, int R, int S,
+                                 int Ho, int Wo, int sh, int sw, int ph, int pw, const float *bias,
+                                 int relu, float *y, hipStream_t st);
+
+// ---- conv_si.hip
+constexpr int kSiCC = 16;
+bool si_tiled_supported(int K, int C, int R, int S, int sh, int sw);
+hipError_t launch_conv_si(const fscnn_input *in, const float *w, int K, int R, int S, int Ho, int Wo,
+                          int sh, int sw, int ph, int pw, const float *bias, int relu, float *y,
+                          hipStream_t st);
+
+}  // namespace fscnn

@@ -1,0 +1,283 @@
+"""Thin ctypes binding of libfscnn.so (C ABI in include/fscnn.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch is used for device memory (`data_ptr()`) and the current
+stream.  There is no CPU fallback: if the library has not been built, or a call
+returns an error status, an exception is raised.
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfscnn.so")
+_lib = None
+
+OK = 0
+STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_MISMATCH", 4: "ERR_UNSUPPORTED",
+                5: "ERR_ALLOC", 6: "ERR_DEVICE", 7: "ERR_HANDLE"}
+
+# every symbol include/fscnn.h declares
+EXPORTS = [
+    "fscnn_status_string", "fscnn_conv2d_out_shape", "fscnn_filter_compress", "fscnn_filter_info",
+    "fscnn_filter_export", "fscnn_filter_prepare", "fscnn_filter_plan_export",
+    "fscnn_filter_destroy", "fscnn_sf_variant_count", "fscnn_sf_variant_name",
+    "fscnn_conv2d_sparse_filter", "fscnn_conv2d_sparse_filter_v", "fscnn_input_compress",
+    "fscnn_input_info", "fscnn_input_export", "fscnn_input_destroy", "fscnn_conv2d_sparse_input",
+    "fscnn_maxpool2x2",
+]
+
+
+class FscnnError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = int(status)
+        msg = lib().fscnn_status_string(self.status).decode()
+        super().__init__("%s: %s (%s)" % (what, STATUS_NAMES.get(self.status, self.status), msg))
+
+
+def lib():
+    """Loads libfscnn.so; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libfscnn.so is missing: run `python -m paper_2212_08815_amd.build` "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.fscnn_status_string.restype = ctypes.c_char_p
+        L.fscnn_status_string.argtypes = [ctypes.c_int]
+        L.fscnn_sf_variant_name.restype = ctypes.c_char_p
+        L.fscnn_sf_variant_name.argtypes = [ctypes.c_int]
+        L.fscnn_sf_variant_count.restype = ctypes.c_int
+        for name in EXPORTS:
+            fn = getattr(L, name)
+            if name not in ("fscnn_status_string", "fscnn_sf_variant_name", "fscnn_sf_variant_count"):
+                fn.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status, what):
+    if status != OK:
+        raise FscnnError(status, what)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_f32(t, name):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous float32 CUDA tensor" % name)
+    return t
+
+
+def _i(v):
+    return ctypes.c_int(int(v))
+
+
+def conv2d_out_shape(H, W, R, S, stride=(1, 1), pad=(0, 0)):
+    ho, wo = ctypes.c_int(), ctypes.c_int()
+    _check(lib().fscnn_conv2d_out_shape(_i(H), _i(W), _i(R), _i(S), _i(stride[0]), _i(stride[1]),
+                                        _i(pad[0]), _i(pad[1]), ctypes.byref(ho), ctypes.byref(wo)),
+           "fscnn_conv2d_out_shape")
+    return ho.value, wo.value
+
+
+def sf_variant_count():
+    return int(lib().fscnn_sf_variant_count())
+
+
+def sf_variant_name(v):
+    return lib().fscnn_sf_variant_name(int(v)).decode()
+
+
+class SparseFilter:
+    """Owner of a fscnn_filter_t handle."""
+
+    def __init__(self, handle, shape, nnz):
+        self._h = handle
+        self.shape = shape
+        self.nnz = nnz
+
+    def __del__(self):
+        self.destroy()
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            lib().fscnn_filter_destroy(self._h)
+            self._h = None
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise RuntimeError("filter handle already destroyed")
+        return self._h
+
+
+def filter_compress(w):
+    """fscnn_filter_compress: dense K x C x R x S float32 CUDA tensor -> SparseFilter."""
+    w = _dev_f32(w, "w")
+    if w.dim() != 4:
+        raise TypeError("w must be K x C x R x S")
+    K, C, R, S = w.shape
+    h = ctypes.c_void_p()
+    _check(lib().fscnn_filter_compress(_ptr(w), _i(K), _i(C), _i(R), _i(S), _stream(), ctypes.byref(h)),
+           "fscnn_filter_compress")
+    nnz = ctypes.c_longlong()
+    _check(lib().fscnn_filter_info(h, None, None, None, None, ctypes.byref(nnz)), "fscnn_filter_info")
+    return SparseFilter(h, (K, C, R, S), nnz.value)
+
+
+def filter_export(f):
+    """fscnn_filter_export -> (rowptr int32[K+1], idx uint32[nnz], val float32[nnz]) numpy."""
+    K = f.shape[0]
+    rowptr = np.empty(K + 1, np.int32)
+    idx = np.empty(f.nnz, np.uint32)
+    val = np.empty(f.nnz, np.float32)
+    _check(lib().fscnn_filter_export(f.handle, rowptr.ctypes.data_as(ctypes.c_void_p),
+                                     idx.ctypes.data_as(ctypes.c_void_p),
+                                     val.ctypes.data_as(ctypes.c_void_p)), "fscnn_filter_export")
+    return rowptr, idx, val
+
+
+def filter_prepare(f, N, H, W, stride=(1, 1), pad=(0, 0), variant=0):
+    _check(lib().fscnn_filter_prepare(f.handle, _i(N), _i(H), _i(W), _i(stride[0]), _i(stride[1]),
+                                      _i(pad[0]), _i(pad[1]), _i(variant), _stream()),
+           "fscnn_filter_prepare")
+
+
+def filter_plan_export(f, N, H, W, stride=(1, 1), pad=(0, 0), variant=0):
+    """fscnn_filter_plan_export -> dict(params..., segptr, rec_off, rec_val)."""
+    params = np.zeros(16, np.int32)
+    args = (f.handle, _i(N), _i(H), _i(W), _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]),
+            _i(variant))
+    _check(lib().fscnn_filter_plan_export(*args, params.ctypes.data_as(ctypes.c_void_p), None, None, None),
+           "fscnn_filter_plan_export")
+    out = dict(variant=int(params[0]), CC=int(params[1]), KG=int(params[2]), NCH=int(params[3]),
+               NG=int(params[4]), NSLOT=int(params[5]), PITCH=int(params[6]), VW=int(params[7]),
+               nrec=int(params[8]), direct=bool(params[9]))
+    if out["direct"]:
+        return out
+    nb = out["NG"] * out["NCH"] * out["KG"]
+    segptr = np.empty(nb + 1, np.int32)
+    off = np.empty(out["nrec"], np.uint32)
+    val = np.empty(out["nrec"], np.float32)
+    _check(lib().fscnn_filter_plan_export(*args, params.ctypes.data_as(ctypes.c_void_p),
+                                          segptr.ctypes.data_as(ctypes.c_void_p),
+                                          off.ctypes.data_as(ctypes.c_void_p),
+                                          val.ctypes.data_as(ctypes.c_void_p)),
+           "fscnn_filter_plan_export")
+    out.update(segptr=segptr, rec_off=off, rec_val=val)
+    return out
+
+
+def conv2d_sparse_filter(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=False, out=None, variant=0):
+    """fscnn_conv2d_sparse_filter(_v): x N x C x H x W -> y N x K x Ho x Wo (both CUDA float32)."""
+    x = _dev_f32(x, "x")
+    bias = _dev_f32(bias, "bias")
+    if x.dim() != 4:
+        raise TypeError("x must be N x C x H x W")
+    N, C, H, W = x.shape
+    K, _, R, S = f.shape
+    Ho, Wo = conv2d_out_shape(H, W, R, S, stride, pad)
+    if out is None:
+        out = torch.empty((N, K, Ho, Wo), dtype=torch.float32, device=x.device)
+    else:
+        _dev_f32(out, "out")
+        if tuple(out.shape) != (N, K, Ho, Wo):
+            raise TypeError("out has the wrong shape")
+    if bias is not None and bias.numel() != K:
+        raise TypeError("bias must have K entries")
+    _check(lib().fscnn_conv2d_sparse_filter_v(f.handle, _ptr(x), _i(N), _i(C), _i(H), _i(W),
+                                              _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]),
+                                              _ptr(bias), _i(bool(relu)), _ptr(out), _i(variant),
+                                              _stream()), "fscnn_conv2d_sparse_filter")
+    return out
+
+
+class SparseInput:
+    """Owner of a fscnn_input_t handle."""
+
+    def __init__(self, handle, shape, nnz):
+        self._h = handle
+        self.shape = shape
+        self.nnz = nnz
+
+    def __del__(self):
+        self.destroy()
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            lib().fscnn_input_destroy(self._h)
+            self._h = None
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise RuntimeError("input handle already destroyed")
+        return self._h
+
+
+def input_compress(x):
+    """fscnn_input_compress: dense N x C x H x W float32 CUDA tensor -> SparseInput."""
+    x = _dev_f32(x, "x")
+    if x.dim() != 4:
+        raise TypeError("x must be N x C x H x W")
+    N, C, H, W = x.shape
+    h = ctypes.c_void_p()
+    _check(lib().fscnn_input_compress(_ptr(x), _i(N), _i(C), _i(H), _i(W), _stream(), ctypes.byref(h)),
+           "fscnn_input_compress")
+    nnz = ctypes.c_longlong()
+    _check(lib().fscnn_input_info(h, None, None, None, None, ctypes.byref(nnz)), "fscnn_input_info")
+    return SparseInput(h, (N, C, H, W), nnz.value)
+
+
+def input_export(s):
+    N, C, H, W = s.shape
+    prow = np.empty(N * H * W + 1, np.int32)
+    cidx = np.empty(s.nnz, np.uint32)
+    val = np.empty(s.nnz, np.float32)
+    _check(lib().fscnn_input_export(s.handle, prow.ctypes.data_as(ctypes.c_void_p),
+                                    cidx.ctypes.data_as(ctypes.c_void_p),
+                                    val.ctypes.data_as(ctypes.c_void_p)), "fscnn_input_export")
+    return prow, cidx, val
+
+
+def conv2d_sparse_input(s, w, stride=(1, 1), pad=(0, 0), bias=None, relu=False, out=None):
+    """fscnn_conv2d_sparse_input: compressed x, dense w K x C x R x S -> y N x K x Ho x Wo."""
+    w = _dev_f32(w, "w")
+    bias = _dev_f32(bias, "bias")
+    N, C, H, W = s.shape
+    if w.dim() != 4 or w.shape[1] != C:
+        raise TypeError("w must be K x C x R x S with C matching the input")
+    K, _, R, S = w.shape
+    Ho, Wo = conv2d_out_shape(H, W, R, S, stride, pad)
+    if out is None:
+        out = torch.empty((N, K, Ho, Wo), dtype=torch.float32, device=w.device)
+    elif tuple(out.shape) != (N, K, Ho, Wo):
+        raise TypeError("out has the wrong shape")
+    if bias is not None and bias.numel() != K:
+        raise TypeError("bias must have K entries")
+    _check(lib().fscnn_conv2d_sparse_input(s.handle, _ptr(w), _i(K), _i(R), _i(S), _i(stride[0]),
+                                           _i(stride[1]), _i(pad[0]), _i(pad[1]), _ptr(bias),
+                                           _i(bool(relu)), _ptr(_dev_f32(out, "out")), _stream()),
+           "fscnn_conv2d_sparse_input")
+    return out
+
+
+def maxpool2x2(x, out=None):
+    x = _dev_f32(x, "x")
+    N, C, H, W = x.shape
+    if out is None:
+        out = torch.empty((N, C, H // 2, W // 2), dtype=torch.float32, device=x.device)
+    _check(lib().fscnn_maxpool2x2(_ptr(x), _i(N), _i(C), _i(H), _i(W), _ptr(out), _stream()),
+           "fscnn_maxpool2x2")
+    return out

@@ -1,0 +1,391 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Integer / index work must match bit for bit; fp32 results within
+the rule of tests/parity.py."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2212_08815_amd import inputs
+from parity import assert_parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def F():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2212_08815_amd import fscnn
+    fscnn.lib()          # raises if libfscnn.so was not built: no fallback
+    return fscnn
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def bits(a):
+    return np.ascontiguousarray(a, np.float32).view(np.uint32)
+
+
+def row_nmax(w):
+    return int(np.count_nonzero(w.reshape(w.shape[0], -1), axis=1).max())
+
+
+def gpu_conv(F, x, w, stride, pad, bias, relu, variant=0, filt=None):
+    f = filt or F.filter_compress(dev(w))
+    y = F.conv2d_sparse_filter(f, dev(x), stride, pad, dev(bias), relu, variant=variant)
+    torch.cuda.synchronize()
+    return host(y)
+
+
+def tiled_variants(F):
+    return list(range(1, F.sf_variant_count() + 1))
+
+
+# ------------------------------------------------------------------ A1/A2: filter compression
+@pytest.mark.parametrize("shape,keep", [((32, 16, 3, 3), 0.1), ((5, 7, 3, 3), 0.5), ((3, 2, 5, 4), 1.0),
+                                        ((130, 33, 1, 1), 0.3), ((64, 300, 3, 3), 0.05), ((2, 1, 1, 1), 0.5)])
+def test_filter_compress_bit_exact(F, shape, keep):
+    _, w, _ = inputs.random_layer(sum(shape), 1, shape[1], shape[0], 4, 4, shape[2], shape[3], keep)
+    f = F.filter_compress(dev(w))
+    rp, ix, vl = F.filter_export(f)
+    orp, oix, ovl = oracle.filter_compress(w)
+    assert f.nnz == orp[-1]
+    assert np.array_equal(rp, orp) and np.array_equal(ix, oix) and np.array_equal(bits(vl), bits(ovl))
+
+
+def test_filter_compress_special_values_and_empty_rows(F):
+    w = np.zeros((4, 3, 3, 3), np.float32)
+    w[0, 0, 0, 1] = -0.0
+    w[0, 1, 0, 0] = np.nan
+    w[1, 0, 0, 2] = np.float32(1e-42)
+    w[3, 2, 2, 2] = -3.5
+    f = F.filter_compress(dev(w))
+    rp, ix, vl = F.filter_export(f)
+    orp, oix, ovl = oracle.filter_compress(w)
+    assert list(rp) == list(orp) == [0, 1, 2, 2, 3]
+    assert np.array_equal(ix, oix) and np.array_equal(bits(vl), bits(ovl))
+    z = F.filter_compress(dev(np.zeros((3, 2, 3, 3), np.float32)))
+    rp, ix, vl = F.filter_export(z)
+    assert z.nnz == 0 and list(rp) == [0, 0, 0, 0] and ix.size == 0
+    # an all-zero bank convolves to bias (then ReLU)
+    x = np.random.default_rng(0).standard_normal((2, 2, 9, 70)).astype(np.float32)
+    b = np.array([-1.0, 0.5, 2.0], np.float32)
+    y = host(F.conv2d_sparse_filter(z, dev(x), (1, 1), (1, 1), dev(b), True))
+    assert np.array_equal(y, np.broadcast_to(np.maximum(b, 0)[None, :, None, None], y.shape))
+
+
+# ------------------------------------------------------------------ A3: regrouped plan
+def test_plan_regroup_decodes_to_the_canonical_rows(F):
+    _, w, _ = inputs.random_layer(21, 1, 37, 70, 4, 4, 3, 3, keep=0.15)
+    K, C, R, S = w.shape
+    f = F.filter_compress(dev(w))
+    orp, oix, ovl = oracle.filter_compress(w)
+    for v in tiled_variants(F):
+        p = F.filter_plan_export(f, 1, 30, 30, (1, 1), (1, 1), variant=v)
+        assert not p["direct"] and p["variant"] == v
+        CC, KG, NCH, NG = p["CC"], p["KG"], p["NCH"], p["NG"]
+        assert NCH == -(-C // CC) and NG == -(-K // KG)
+        seg = p["segptr"]
+        assert seg[0] == 0 and np.all(np.diff(seg) >= 0) and seg[-1] == orp[-1]
+        q = p["rec_off"].astype(np.int64) // (4 * p["VW"])
+        assert np.all(p["rec_off"] % (4 * p["VW"]) == 0)
+        s = q % p["PITCH"]
+        r = (q // p["PITCH"]) % p["NSLOT"]
+        cl = q // (p["PITCH"] * p["NSLOT"])
+        for g in range(NG):
+            for ci in range(NCH):
+                for kk in range(KG):
+                    b = (g * NCH + ci) * KG + kk
+                    k = g * KG + kk
+                    lo, hi = seg[b], seg[b + 1]
+                    if k >= K:
+                        assert lo == hi
+                        continue
+                    row = slice(orp[k], orp[k + 1])
+                    flat = oix[row].astype(np.int64)
+                    sel = (flat // (R * S)) // CC == ci        # entries of this chunk, in row order
+                    want_flat = flat[sel]
+                    got_flat = ((cl[lo:hi] + ci * CC) * R + r[lo:hi]) * S + s[lo:hi]
+                    assert np.array_equal(got_flat, want_flat)
+                    assert np.all(cl[lo:hi] < CC) and np.all(r[lo:hi] < R) and np.all(s[lo:hi] < S)
+                    assert np.array_equal(bits(p["rec_val"][lo:hi]), bits(ovl[row][sel]))
+
+
+# ------------------------------------------------------------------ A4-A6: tiled convolution
+CASES = [
+    # n, c, k, h, w, keep, pad, bias, relu
+    (1, 16, 32, 32, 32, 0.10, (1, 1), False, False),
+    (2, 19, 37, 23, 71, 0.30, (1, 1), True, True),      # ragged everything, several tiles in x
+    (1, 3, 64, 40, 130, 1.00, (1, 1), True, True),      # dense first-layer shape, 3 tiles in x
+    (3, 40, 9, 14, 14, 0.20, (1, 1), True, False),
+    (1, 33, 65, 17, 29, 0.05, (0, 0), True, True),      # no padding: output smaller than input
+    (1, 8, 8, 9, 9, 0.50, (2, 2), False, True),         # pad wider than the halo of a 3x3
+    (2, 64, 64, 28, 28, 0.05, (1, 1), True, True),
+    (1, 5, 4, 3, 3, 0.60, (1, 1), True, False),         # image smaller than any tile
+    (1, 2, 3, 1, 1, 1.00, (1, 1), True, False),         # 1x1 image
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_conv_sparse_filter_matches_oracle_all_variants(F, case):
+    n, c, k, h, w_, keep, pad, use_b, relu = case
+    x, w, b = inputs.random_layer(hash(case) % 1000, n, c, k, h, w_, 3, 3, keep, bias=use_b)
+    csr = oracle.filter_compress(w)
+    o, a = oracle.conv2d_sparse_filter(x, csr, w.shape, (1, 1), pad, b, relu, want_abs=True)
+    f = F.filter_compress(dev(w))
+    for v in [0] + tiled_variants(F):
+        g = gpu_conv(F, x, w, (1, 1), pad, b, relu, variant=v, filt=f)
+        assert_parity(g, o, a, row_nmax(w), "case %r variant %d" % (case, v))
+
+
+def test_integer_data_is_bit_exact_all_variants(F):
+    # every partial sum is an exact small integer: any summation order gives the same bits
+    x, w, b = inputs.random_layer(31, 2, 21, 34, 19, 67, 3, 3, keep=0.3, integer=True)
+    o = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, (1, 1), (1, 1), b, True)
+    f = F.filter_compress(dev(w))
+    for v in [0] + tiled_variants(F):
+        g = gpu_conv(F, x, w, (1, 1), (1, 1), b, True, variant=v, filt=f)
+        assert np.array_equal(g, o), "variant %d" % v
+
+
+def test_impulses_pin_orientation_on_the_gpu(F):
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((1, 20, 11, 70)).astype(np.float32)
+    for (k0, c0, r0, s0) in [(0, 0, 0, 0), (5, 17, 2, 1), (8, 19, 1, 2), (2, 16, 0, 2)]:
+        w = np.zeros((9, 20, 3, 3), np.float32)
+        w[k0, c0, r0, s0] = 1.0
+        f = F.filter_compress(dev(w))
+        for v in [0] + tiled_variants(F):
+            y = gpu_conv(F, x, w, (1, 1), (1, 1), None, False, variant=v, filt=f)
+            xp = np.pad(x[0, c0], 1)
+            want = xp[r0:r0 + 11, s0:s0 + 70]
+            assert np.array_equal(y[0, k0], want), (k0, c0, r0, s0, v)
+            assert not np.delete(y[0], k0, axis=0).any()
+    # single input pixel: the output patch around it is the un-flipped filter read backwards
+    w = rng.standard_normal((4, 3, 3, 3)).astype(np.float32)
+    xi = np.zeros((1, 3, 12, 12), np.float32)
+    xi[0, 1, 6, 5] = 1.0
+    y = gpu_conv(F, xi, w, (1, 1), (1, 1), None, False)
+    assert np.array_equal(y[0, :, 5:8, 4:7], w[:, 1, ::-1, ::-1])
+
+
+def test_dense_filter_equals_dense_convolution(F):
+    x, w, b = inputs.random_layer(41, 1, 12, 10, 20, 66, 3, 3, keep=1.0)
+    o, a = oracle.conv2d_dense(x, w, (1, 1), (1, 1), b, False, want_abs=True)
+    f = F.filter_compress(dev(w))
+    assert f.nnz == w.size
+    assert_parity(gpu_conv(F, x, w, (1, 1), (1, 1), b, False, filt=f), o, a, row_nmax(w), "dense")
+
+
+# ------------------------------------------------------------------ direct kernel (any stride / extent)
+@pytest.mark.parametrize("r,s,stride,pad", [(1, 1, (1, 1), (0, 0)), (3, 3, (2, 2), (1, 1)), (5, 5, (1, 1), (2, 2)),
+                                            (7, 7, (2, 2), (3, 3)), (2, 4, (1, 3), (0, 2)), (3, 3, (1, 2), (1, 0))])
+def test_direct_kernel_matches_oracle(F, r, s, stride, pad):
+    x, w, b = inputs.random_layer(50 + r * s, 2, 10, 13, 21, 75, r, s, keep=0.3)
+    o, a = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, stride, pad, b, True, want_abs=True)
+    f = F.filter_compress(dev(w))
+    p = F.filter_plan_export(f, 2, 21, 75, stride, pad)
+    assert p["direct"]
+    assert_parity(gpu_conv(F, x, w, stride, pad, b, True, filt=f), o, a, row_nmax(w), "direct")
+
+
+def test_one_by_one_is_matrix_product_on_the_gpu(F):
+    x, w, _ = inputs.random_layer(61, 2, 24, 17, 9, 70, 1, 1, keep=0.4, integer=True, bias=False)
+    g = gpu_conv(F, x, w, (1, 1), (0, 0), None, False)
+    want = np.einsum("kc,ncp->nkp", w[:, :, 0, 0].astype(np.float64),
+                     x.reshape(2, 24, -1).astype(np.float64)).reshape(2, 17, 9, 70)
+    assert np.array_equal(g, want.astype(np.float32))
+
+
+# ------------------------------------------------------------------ error paths with a device present
+def test_error_statuses_on_the_gpu(F):
+    _, w, _ = inputs.random_layer(70, 1, 4, 4, 4, 4, 3, 3, keep=0.5)
+    f = F.filter_compress(dev(w))
+    x = torch.zeros(1, 5, 8, 8, device="cuda")
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_filter(f, x, (1, 1), (1, 1))
+    assert e.value.status == 3                                     # C mismatch
+    x4 = torch.zeros(1, 4, 8, 8, device="cuda")
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_filter(f, x4, (2, 2), (1, 1), variant=1)   # tiled variant cannot stride
+    assert e.value.status == 4
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_filter(f, x4, (1, 1), (1, 1), variant=999)
+    assert e.value.status == 4
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_out_shape(2, 2, 3, 3)
+    assert e.value.status == 2
+    L = F.lib()
+    h = f.handle
+    f._h = None
+    assert L.fscnn_filter_destroy(h) == 0
+    # (a destroyed handle must not be touched again: its memory is gone)
+
+
+# ------------------------------------------------------------------ workload configs
+def test_config1_whole_layer(F):
+    c = inputs.config1()
+    o, a = oracle.conv2d_sparse_filter(c["x"], oracle.filter_compress(c["w"]), c["w"].shape, c["stride"],
+                                       c["pad"], c["bias"], c["relu"], want_abs=True)
+    for v in [0] + tiled_variants(F):
+        g = gpu_conv(F, c["x"], c["w"], c["stride"], c["pad"], c["bias"], c["relu"], variant=v)
+        assert_parity(g, o, a, row_nmax(c["w"]), "config1 v%d" % v)
+
+
+def test_config2_whole_layer(F):
+    c = inputs.config2()
+    csr = oracle.filter_compress(c["w"])
+    f = F.filter_compress(dev(c["w"]))
+    rp, ix, vl = F.filter_export(f)
+    assert np.array_equal(rp, csr[0]) and np.array_equal(ix, csr[1]) and np.array_equal(bits(vl), bits(csr[2]))
+    o, a = oracle.conv2d_sparse_filter(c["x"], csr, c["w"].shape, c["stride"], c["pad"], c["bias"], c["relu"],
+                                       want_abs=True)
+    for v in [0] + tiled_variants(F):
+        g = gpu_conv(F, c["x"], c["w"], c["stride"], c["pad"], c["bias"], c["relu"], variant=v, filt=f)
+        assert_parity(g, o, a, row_nmax(c["w"]), "config2 v%d" % v)
+
+
+def _run_stack(F, x, layers, check):
+    """Runs the conv (+pool) chain on the GPU, calling check(li, x_in_host, layer, y_host)."""
+    cur = dev(x)
+    for li, L in enumerate(layers):
+        f = F.filter_compress(dev(L["w"]))
+        y = F.conv2d_sparse_filter(f, cur, L["stride"], L["pad"], dev(L["bias"]), L["relu"])
+        torch.cuda.synchronize()
+        check(li, host(cur), L, host(y), f)
+        cur = F.maxpool2x2(y) if L["pool_after"] else y
+        del f
+    return cur
+
+
+def test_config3_reduced_size_chain_whole_tensors(F):
+    # the 13-layer VGG16-shaped stack at 56x56 input (224/4) so that the oracle runs every layer
+    # in full; each layer is compared against the oracle fed the GPU's previous output, and the
+    # final tensor against the oracle's own chain
+    x, layers = inputs.config3(size_div=4)
+    state = {"o": x}
+
+    def check(li, xin, L, y, f):
+        csr = oracle.filter_compress(L["w"])
+        rp, ix, vl = F.filter_export(f)
+        assert np.array_equal(rp, csr[0]) and np.array_equal(ix, csr[1]) and np.array_equal(bits(vl), bits(csr[2]))
+        o, a = oracle.conv2d_sparse_filter(xin, csr, L["w"].shape, L["stride"], L["pad"], L["bias"], L["relu"],
+                                           want_abs=True)
+        assert_parity(y, o, a, row_nmax(L["w"]), "config3/4 layer %d (GPU-fed)" % li)
+        oo = oracle.conv2d_sparse_filter(state["o"], csr, L["w"].shape, L["stride"], L["pad"], L["bias"], L["relu"])
+        state["o"] = oracle.maxpool2x2(oo) if L["pool_after"] else oo
+        state["last"] = oo
+        state["last_gpu"] = y
+
+    _run_stack(F, x, layers, check)
+    # the whole chain against the oracle's own chain: rounding differences compound over the 13
+    # layers (and can flip a ReLU), so this end-to-end figure is held to 1e-3 instead of 1e-4
+    from parity import rel_err
+    assert state["last"].shape == (1, 512, 3, 3)
+    assert rel_err(state["last_gpu"], state["last"]) <= 1e-3
+
+
+def _sampled_layer_check(F, rng, npts):
+    def check(li, xin, L, y, f):
+        flat = rng.choice(y.size, size=min(npts, y.size), replace=False)
+        # always include the corners and the last element (tile and image borders)
+        flat = np.unique(np.concatenate([flat, [0, y.shape[3] - 1, y.size - 1, y.size - y.shape[3]]]))
+        o, a = oracle.conv2d_points(xin, L["w"], flat, L["stride"], L["pad"], L["bias"], L["relu"], want_abs=True)
+        assert_parity(y.ravel()[flat], o, a, row_nmax(L["w"]), "layer %d sampled" % li)
+        # properties that hold at any size: ReLU output is non-negative and finite everywhere
+        assert np.all(np.isfinite(y)) and y.min() >= 0.0
+    return check
+
+
+def test_config3_full_size_sampled(F):
+    x, layers = inputs.config3()
+    out = _run_stack(F, x, layers, _sampled_layer_check(F, np.random.default_rng(3), 4000))
+    assert tuple(out.shape) == (1, 512, 14, 14)
+
+
+def test_config4_full_size_sampled(F):
+    x, layers = inputs.config4(n=32)
+    out = _run_stack(F, x, layers, _sampled_layer_check(F, np.random.default_rng(4), 4000))
+    assert tuple(out.shape) == (32, 512, 14, 14)
+
+
+@pytest.mark.parametrize("keep", inputs.CONFIG5_KEEP)
+def test_config5_sparsity_sweep_sampled(F, keep):
+    c = inputs.config5(keep)
+    f = F.filter_compress(dev(c["w"]))
+    y = host(F.conv2d_sparse_filter(f, dev(c["x"]), c["stride"], c["pad"], dev(c["bias"]), c["relu"]))
+    flat = np.random.default_rng(5).choice(y.size, 3000, replace=False)
+    o, a = oracle.conv2d_points(c["x"], c["w"], flat, c["stride"], c["pad"], c["bias"], c["relu"], want_abs=True)
+    assert_parity(y.ravel()[flat], o, a, row_nmax(c["w"]), "config5 keep %g" % keep)
+
+
+# ------------------------------------------------------------------ A7/A8: sparse-input path
+@pytest.mark.parametrize("shape,zf", [((2, 7, 5, 6), 0.7), ((1, 40, 9, 70), 0.5), ((3, 16, 1, 1), 0.0),
+                                      ((1, 33, 4, 4), 1.0)])
+def test_input_compress_bit_exact(F, shape, zf):
+    n, c, h, w_ = shape
+    x, _, _ = inputs.random_layer(80 + c, n, c, 1, h, w_, 1, 1, 1.0, x_zero_frac=zf)
+    if zf == 0.7:
+        x[0, 0, 0, 0] = -0.0
+        x[0, 1, 0, 0] = np.nan
+    s = F.input_compress(dev(x))
+    prow, cidx, val = F.input_export(s)
+    op, oc, ov = oracle.input_compress(x)
+    assert s.nnz == op[-1]
+    assert np.array_equal(prow, op) and np.array_equal(cidx, oc) and np.array_equal(bits(val), bits(ov))
+
+
+@pytest.mark.parametrize("case", [
+    (2, 19, 37, 11, 23, 3, 3, (1, 1), (1, 1)),
+    (1, 40, 70, 14, 14, 3, 3, (1, 1), (1, 1)),
+    (1, 16, 64, 9, 9, 3, 3, (1, 1), (0, 0)),
+    (2, 10, 13, 12, 15, 3, 3, (2, 2), (1, 1)),       # direct kernel
+    (1, 6, 5, 8, 8, 1, 1, (1, 1), (0, 0)),           # direct kernel
+    (1, 7, 66, 10, 9, 5, 2, (1, 2), (2, 0)),         # direct kernel
+])
+def test_conv_sparse_input_matches_oracle(F, case):
+    n, c, k, h, w_, r, s_, stride, pad = case
+    x, w, b = inputs.random_layer(90 + c + k, n, c, k, h, w_, r, s_, keep=0.5, x_zero_frac=0.7)
+    csx = oracle.input_compress(x)
+    o, a = oracle.conv2d_sparse_input(csx, x.shape, w, stride, pad, b, True, want_abs=True)
+    s = F.input_compress(dev(x))
+    g = host(F.conv2d_sparse_input(s, dev(w), stride, pad, dev(b), True))
+    assert_parity(g, o, a, c * r * s_, "sparse input %r" % (case,))
+    # three-way agreement: the sparse-filter path on the same data
+    g2 = gpu_conv(F, x, w, stride, pad, b, True)
+    assert_parity(g2, o, a, c * r * s_, "sparse filter on the same data")
+
+
+def test_sparse_input_integer_bit_exact(F):
+    x, w, b = inputs.random_layer(95, 2, 21, 70, 13, 18, 3, 3, keep=0.6, x_zero_frac=0.6, integer=True)
+    o = oracle.conv2d_dense(x, w, (1, 1), (1, 1), b, True)
+    g = host(F.conv2d_sparse_input(F.input_compress(dev(x)), dev(w), (1, 1), (1, 1), dev(b), True))
+    assert np.array_equal(g, o)
+
+
+def test_config5_sparse_input_point(F):
+    c = inputs.config5(0.05)
+    xs = F.input_compress(dev(c["x"]))
+    op, oc, ov = oracle.input_compress(c["x"])
+    prow, cidx, val = F.input_export(xs)
+    assert np.array_equal(prow, op) and np.array_equal(cidx, oc) and np.array_equal(bits(val), bits(ov))
+    assert 0.29 < xs.nnz / c["x"].size < 0.33          # ReLU(N(-0.5,1)) keeps ~30.85 %
+    y = host(F.conv2d_sparse_input(xs, dev(c["w"]), c["stride"], c["pad"], dev(c["bias"]), c["relu"]))
+    flat = np.random.default_rng(6).choice(y.size, 3000, replace=False)
+    o, a = oracle.conv2d_points(c["x"], c["w"], flat, c["stride"], c["pad"], c["bias"], c["relu"], want_abs=True)
+    assert_parity(y.ravel()[flat], o, a, 512 * 9, "config5 sparse input")
+
+
+# ------------------------------------------------------------------ helper
+def test_maxpool_helper(F):
+    x = np.random.default_rng(1).standard_normal((2, 5, 13, 22)).astype(np.float32)
+    assert np.array_equal(host(F.maxpool2x2(dev(x))), oracle.maxpool2x2(x))
