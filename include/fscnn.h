@@ -44,6 +44,17 @@ typedef enum {
 
 const char *fscnn_status_string(fscnn_status_t s);
 
+/* Memory layout of a 4-D activation tensor of N images.
+ *   FSCNN_LAYOUT_NCHW: element (n,c,h,w) at ((n*C + c)*H + h)*W + w.
+ *   FSCNN_LAYOUT_N4:   batch-interleaved by four: element (n,c,h,w) at
+ *                      ((((n/4)*C + c)*H + h)*W + w)*4 + n%4; the buffer holds 4*ceil(N/4)
+ *                      images and must be 16-byte aligned; the contents of the images past N are
+ *                      unspecified on output and ignored on input.  This is the layout the
+ *                      convolution kernel keeps in LDS (one 16-byte read feeds four images), so
+ *                      chained layers that pass N4 tensors stage their input with contiguous
+ *                      16-byte loads and store their output with 16-byte stores. */
+typedef enum { FSCNN_LAYOUT_NCHW = 0, FSCNN_LAYOUT_N4 = 1 } fscnn_layout_t;
+
 /* Output extent of a convolution (host only).  Alg. 1 step 3 and Alg. 6 step 3 give
  * (H_I - H_F)/S + 1; with the symmetric zero padding of Sec. 5 ("Other layers") this is
  * floor((H + 2*pad - R)/stride) + 1.  FSCNN_ERR_SHAPE if any size is non-positive, a pad
@@ -72,12 +83,13 @@ fscnn_status_t fscnn_filter_export(const fscnn_filter_t *f, int *rowptr_host,
                                    unsigned *idx_host, float *val_host);
 
 /* Builds (once) the device-side plan the convolution kernel streams for this geometry:
- * the nonzeros regrouped by (output-channel group, input-channel chunk, output channel)
+ * the nonzeros regrouped by (output-channel group, wave, input-channel chunk, channel slot)
  * with each (c,r,s) packed into the byte offset of that tap inside the LDS input tile.
- * Allocates device memory and launches on `stream` (no synchronisation).  Optional:
+ * Allocates device memory, launches on `stream` and synchronises it once.  Optional:
  * fscnn_conv2d_sparse_filter builds the plan on first use; after that (or after this
- * call) convolution calls with the same geometry allocate nothing.  `variant` selects a
- * kernel configuration (0 = automatic choice; see fscnn_sf_variant_count). */
+ * call) convolution calls served by the same kernel configuration allocate nothing and do
+ * not synchronise.  `variant` selects a kernel configuration (0 = automatic choice; see
+ * fscnn_sf_variant_count). */
 fscnn_status_t fscnn_filter_prepare(fscnn_filter_t *f, int N, int H, int W, int stride_h,
                                     int stride_w, int pad_h, int pad_w, int variant,
                                     void *stream);
@@ -85,9 +97,13 @@ fscnn_status_t fscnn_filter_prepare(fscnn_filter_t *f, int N, int H, int W, int 
 /* Debug / test view of the plan chosen for a geometry (builds it if needed, synchronous).
  * Writes the plan parameters into params_host[16]:
  *   [0] variant id  [1] CC channels per chunk  [2] KG output channels per group
- *   [3] number of chunks  [4] number of groups  [5] slot rows per channel
- *   [6] pitch (elements per row)  [7] vector width VW  [8] records (incl. padding)
- *   [9] 1 if the direct (untiled) kernel serves this geometry, else 0; rest 0.
+ *   [3] number of chunks  [4] number of groups  [5] tile rows per channel
+ *   [6] pitch (vectors per tile row)  [7] BV floats per vector (images interleaved)
+ *   [8] records (= nonzeros)  [9] 1 if the direct (untiled) kernel serves this geometry
+ *   [10] SLOTS channels per wave  [11] WAVES per group (KG = SLOTS*WAVES); rest 0.
+ * Bucket b = ((group*WAVES + wave)*chunks + chunk)*SLOTS + slot holds the entries of output
+ * channel group*KG + wave*SLOTS + slot whose input channel lies in the chunk; a record's
+ * byte offset is (((c mod CC)*rows + r)*pitch + s)*BV*4.
  * If segptr_host / rec_off_host / rec_val_host are non-NULL they receive
  * segptr[groups*chunks*KG + 1], and per record the LDS byte offset and the weight.
  * Pass NULL pointers first to learn the sizes. */
@@ -123,6 +139,22 @@ fscnn_status_t fscnn_conv2d_sparse_filter_v(fscnn_filter_t *f, const float *x_de
                                             int pad_h, int pad_w, const float *bias_dev,
                                             int relu, float *y_dev, int variant, void *stream);
 
+/* Same operation with explicit tensor layouts for x and y (see fscnn_layout_t) and an explicit
+ * kernel configuration (0 = automatic).  N4 tensors need a configuration that keeps four
+ * images per lane (the automatic choice does when N >= 4); FSCNN_ERR_UNSUPPORTED otherwise,
+ * for strides other than 1, or if an N4 pointer is not 16-byte aligned. */
+fscnn_status_t fscnn_conv2d_sparse_filter_ex(fscnn_filter_t *f, const float *x_dev, int N,
+                                             int C, int H, int W, int stride_h, int stride_w,
+                                             int pad_h, int pad_w, const float *bias_dev,
+                                             int relu, float *y_dev, fscnn_layout_t x_layout,
+                                             fscnn_layout_t y_layout, int variant, void *stream);
+
+/* Layout conversion of an N x C x H x W tensor (src_layout != dst_layout, no aliasing).
+ * Asynchronous on `stream`. */
+fscnn_status_t fscnn_layout_convert(const float *src_dev, int N, int C, int H, int W,
+                                    fscnn_layout_t src_layout, float *dst_dev,
+                                    fscnn_layout_t dst_layout, void *stream);
+
 /* ------------------------------------------------------------------ sparse inputs
  * Activation compression (Sec. 3, sparse 3-D tensor in order O_chw: the channel run is the
  * innermost list): one row per pixel in (n, iy, ix) raster order holding the (channel,
@@ -152,6 +184,9 @@ fscnn_status_t fscnn_conv2d_sparse_input(const fscnn_input_t *in, const float *w
  * Only used to chain VGG16-shaped layers; not part of the measured convolution path. */
 fscnn_status_t fscnn_maxpool2x2(const float *x_dev, int N, int C, int H, int W, float *y_dev,
                                 void *stream);
+/* Same on tensors of the given layout (input and output share it). */
+fscnn_status_t fscnn_maxpool2x2_ex(const float *x_dev, int N, int C, int H, int W, float *y_dev,
+                                   fscnn_layout_t layout, void *stream);
 
 #ifdef __cplusplus
 }

@@ -88,18 +88,17 @@ fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan *
     p->NCH = (f->C + g.CC - 1) / g.CC;
     p->NG = (f->K + g.KG - 1) / g.KG;
     const long long nb = (long long)p->NG * p->NCH * g.KG;
-    const long long cap = f->nnz + nb * (g.pad_to - 1);
-    if (!fits_int(nb + 1) || cap >= (1LL << 31)) {
+    const long long cap = f->nnz;
+    if (!fits_int(nb + 1) || cap + kPlanSpare >= (1LL << 31)) {
         delete p;
         return FSCNN_ERR_UNSUPPORTED;
     }
     int *cnt = nullptr;
     hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)nb);
     if (e == hipSuccess) e = hipMalloc(&p->segptr, sizeof(int) * (size_t)(nb + 1));
-    if (e == hipSuccess) e = hipMalloc(&p->recs, sizeof(Rec) * (size_t)(cap > 0 ? cap : 1));
+    if (e == hipSuccess) e = hipMalloc(&p->recs, sizeof(Rec) * (size_t)(cap + kPlanSpare));
     if (e == hipSuccess)
-        e = launch_plan_count(f->rowptr, f->idx, f->K, f->R * f->S, g.CC, g.KG, p->NCH, p->NG,
-                              g.pad_to, cnt, st);
+        e = launch_plan_count(f->rowptr, f->idx, f->K, f->R * f->S, g, p->NCH, p->NG, cnt, st);
     if (e == hipSuccess) e = launch_exclusive_scan(cnt, p->segptr, nb, st);
     if (e == hipSuccess)
         e = launch_plan_fill(f->rowptr, f->idx, f->val, f->K, f->R, f->S, g, p->NCH, p->NG,
@@ -123,7 +122,8 @@ fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan *
 fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int sh, int sw,
                                int variant, int *resolved)
 {
-    const bool tiled_ok = (sh == 1 && sw == 1);
+    // the tiled kernel addresses up to four images' channels with 32-bit byte offsets
+    const bool tiled_ok = (sh == 1 && sw == 1) && (long long)f->C * H * W * 16 < 0x7ffffff0LL;
     if (variant < 0 || variant > sf_variant_count()) return FSCNN_ERR_UNSUPPORTED;
     if (variant > 0) {
         SfGeom g;
@@ -295,10 +295,12 @@ fscnn_status_t fscnn_filter_plan_export(fscnn_filter_t *f, int N, int H, int W, 
     params_host[2] = p->g.KG;
     params_host[3] = p->NCH;
     params_host[4] = p->NG;
-    params_host[5] = p->g.NSLOT;
+    params_host[5] = p->g.IN_ROWS;
     params_host[6] = p->g.PITCH;
-    params_host[7] = p->g.VW;
+    params_host[7] = p->g.BV;
     params_host[8] = (int)p->nrec;
+    params_host[10] = p->g.SLOTS;
+    params_host[11] = p->g.WAVES;
     const long long nb = (long long)p->NG * p->NCH * p->g.KG;
     if (segptr_host)
         FSCNN_HIP(hipMemcpy(segptr_host, p->segptr, sizeof(int) * (size_t)(nb + 1), hipMemcpyDeviceToHost));
@@ -335,17 +337,27 @@ fscnn_status_t fscnn_filter_destroy(fscnn_filter_t *f)
 int fscnn_sf_variant_count(void) { return sf_variant_count(); }
 const char *fscnn_sf_variant_name(int variant) { return sf_variant_name(variant); }
 
-fscnn_status_t fscnn_conv2d_sparse_filter_v(fscnn_filter_t *f, const float *x_dev, int N, int C,
-                                            int H, int W, int sh, int sw, int ph, int pw,
-                                            const float *bias_dev, int relu, float *y_dev,
-                                            int variant, void *stream)
+fscnn_status_t fscnn_conv2d_sparse_filter_ex(fscnn_filter_t *f, const float *x_dev, int N, int C,
+                                             int H, int W, int sh, int sw, int ph, int pw,
+                                             const float *bias_dev, int relu, float *y_dev,
+                                             fscnn_layout_t x_layout, fscnn_layout_t y_layout,
+                                             int variant, void *stream)
 {
     int Ho, Wo;
     fscnn_status_t s = check_conv_args(f, x_dev, N, C, H, W, sh, sw, ph, pw, y_dev, &Ho, &Wo);
     if (s != FSCNN_OK) return s;
+    if ((x_layout != FSCNN_LAYOUT_NCHW && x_layout != FSCNN_LAYOUT_N4) ||
+        (y_layout != FSCNN_LAYOUT_NCHW && y_layout != FSCNN_LAYOUT_N4))
+        return FSCNN_ERR_UNSUPPORTED;
+    const int in4 = x_layout == FSCNN_LAYOUT_N4, out4 = y_layout == FSCNN_LAYOUT_N4;
+    if ((in4 && ((uintptr_t)x_dev & 15)) || (out4 && ((uintptr_t)y_dev & 15))) return FSCNN_ERR_UNSUPPORTED;
+    const long long n4 = ((long long)N + 3) / 4 * 4;
+    if ((in4 && !fits_int(n4 * C * H * W)) || (out4 && !fits_int(n4 * f->K * Ho * Wo)))
+        return FSCNN_ERR_UNSUPPORTED;
     int v;
     s = resolve_variant(f, N, H, W, sh, sw, variant, &v);
     if (s != FSCNN_OK) return s;
+    if ((in4 || out4) && (v < 0 || !sf_variant_has_layout(v, in4, out4))) return FSCNN_ERR_UNSUPPORTED;
     int dev;
     s = have_device(&dev);
     if (s != FSCNN_OK) return s;
@@ -358,8 +370,36 @@ fscnn_status_t fscnn_conv2d_sparse_filter_v(fscnn_filter_t *f, const float *x_de
                                         f->S, Ho, Wo, sh, sw, ph, pw, bias_dev, relu, y_dev, st));
     } else {
         FSCNN_HIP(launch_conv_sf_tiled(*p, x_dev, N, C, H, W, f->K, Ho, Wo, ph, pw, bias_dev, relu,
-                                       y_dev, st));
+                                       y_dev, in4, out4, st));
     }
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_conv2d_sparse_filter_v(fscnn_filter_t *f, const float *x_dev, int N, int C,
+                                            int H, int W, int sh, int sw, int ph, int pw,
+                                            const float *bias_dev, int relu, float *y_dev,
+                                            int variant, void *stream)
+{
+    return fscnn_conv2d_sparse_filter_ex(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, relu, y_dev,
+                                         FSCNN_LAYOUT_NCHW, FSCNN_LAYOUT_NCHW, variant, stream);
+}
+
+fscnn_status_t fscnn_layout_convert(const float *src_dev, int N, int C, int H, int W,
+                                    fscnn_layout_t src_layout, float *dst_dev,
+                                    fscnn_layout_t dst_layout, void *stream)
+{
+    if (!src_dev || !dst_dev) return FSCNN_ERR_NULL;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return FSCNN_ERR_SHAPE;
+    const bool s4 = src_layout == FSCNN_LAYOUT_N4, d4 = dst_layout == FSCNN_LAYOUT_N4;
+    if ((!s4 && src_layout != FSCNN_LAYOUT_NCHW) || (!d4 && dst_layout != FSCNN_LAYOUT_NCHW) ||
+        s4 == d4 || src_dev == dst_dev)
+        return FSCNN_ERR_UNSUPPORTED;
+    if (!fits_int(((long long)N + 3) / 4 * 4 * C * H * W)) return FSCNN_ERR_UNSUPPORTED;
+    if ((uintptr_t)(s4 ? src_dev : dst_dev) & 15) return FSCNN_ERR_UNSUPPORTED;
+    int dev;
+    fscnn_status_t s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    FSCNN_HIP(launch_layout_convert(src_dev, N, C, H, W, s4 ? 1 : 0, dst_dev, (hipStream_t)stream));
     return FSCNN_OK;
 }
 
@@ -488,17 +528,26 @@ fscnn_status_t fscnn_conv2d_sparse_input(const fscnn_input_t *in, const float *w
     return FSCNN_OK;
 }
 
-fscnn_status_t fscnn_maxpool2x2(const float *x_dev, int N, int C, int H, int W, float *y_dev,
-                                void *stream)
+fscnn_status_t fscnn_maxpool2x2_ex(const float *x_dev, int N, int C, int H, int W, float *y_dev,
+                                   fscnn_layout_t layout, void *stream)
 {
     if (!x_dev || !y_dev) return FSCNN_ERR_NULL;
     if (N <= 0 || C <= 0 || H < 2 || W < 2) return FSCNN_ERR_SHAPE;
-    if (!fits_int((long long)N * C * H * W)) return FSCNN_ERR_UNSUPPORTED;
+    if (layout != FSCNN_LAYOUT_NCHW && layout != FSCNN_LAYOUT_N4) return FSCNN_ERR_UNSUPPORTED;
+    const int n4 = layout == FSCNN_LAYOUT_N4;
+    if (!fits_int(((long long)N + 3) / 4 * 4 * C * H * W)) return FSCNN_ERR_UNSUPPORTED;
+    if (n4 && (((uintptr_t)x_dev | (uintptr_t)y_dev) & 15)) return FSCNN_ERR_UNSUPPORTED;
     int dev;
     fscnn_status_t s = have_device(&dev);
     if (s != FSCNN_OK) return s;
-    FSCNN_HIP(launch_maxpool2x2(x_dev, N, C, H, W, y_dev, (hipStream_t)stream));
+    FSCNN_HIP(launch_maxpool2x2(x_dev, N, C, H, W, y_dev, n4, (hipStream_t)stream));
     return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_maxpool2x2(const float *x_dev, int N, int C, int H, int W, float *y_dev,
+                                void *stream)
+{
+    return fscnn_maxpool2x2_ex(x_dev, N, C, H, W, y_dev, FSCNN_LAYOUT_NCHW, stream);
 }
 
 }  // extern "C"

@@ -125,61 +125,70 @@ __device__ inline int lower_bound_u32(const uint32_t *a, int lo, int hi, uint32_
     return lo;
 }
 
+// Bucket b <-> (group g, wave w, chunk ci, slot j), slot fastest: the records of one wave form
+// one contiguous stream ordered by (chunk, slot); its output channel is k = g*KG + w*SLOTS + j.
+struct Bucket {
+    int k, ci;
+};
+__device__ inline Bucket decode_bucket(long long b, int SLOTS, int WAVES, int NCH)
+{
+    Bucket r;
+    const int j = (int)(b % SLOTS);
+    r.ci = (int)((b / SLOTS) % NCH);
+    const int w = (int)((b / ((long long)SLOTS * NCH)) % WAVES);
+    const int g = (int)(b / ((long long)SLOTS * NCH * WAVES));
+    r.k = (g * WAVES + w) * SLOTS + j;
+    return r;
+}
+
 __global__ void plan_count_kernel(const int *__restrict__ rowptr, const uint32_t *__restrict__ idx,
-                                  int K, int RS, int CC, int KG, int NCH, int NG, int pad_to,
+                                  int K, int RS, int CC, int SLOTS, int WAVES, int NCH, int NG,
                                   int *__restrict__ cnt)
 {
     const long long b = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long long nb = (long long)NG * NCH * KG;
+    const long long nb = (long long)NG * NCH * SLOTS * WAVES;
     if (b >= nb) return;
-    const int kk = (int)(b % KG);
-    const int ci = (int)((b / KG) % NCH);
-    const int g = (int)(b / ((long long)KG * NCH));
-    const int k = g * KG + kk;
+    const Bucket q = decode_bucket(b, SLOTS, WAVES, NCH);
     int c = 0;
-    if (k < K) {
-        const int lo = rowptr[k], hi = rowptr[k + 1];
-        const int a = lower_bound_u32(idx, lo, hi, (uint32_t)ci * CC * RS);
-        const int e = lower_bound_u32(idx, lo, hi, (uint32_t)(ci + 1) * CC * RS);
+    if (q.k < K) {
+        const int lo = rowptr[q.k], hi = rowptr[q.k + 1];
+        const int a = lower_bound_u32(idx, lo, hi, (uint32_t)q.ci * CC * RS);
+        const int e = lower_bound_u32(idx, lo, hi, (uint32_t)(q.ci + 1) * CC * RS);
         c = e - a;
-        c = (c + pad_to - 1) / pad_to * pad_to;
     }
     cnt[b] = c;
 }
 
 __global__ void plan_fill_kernel(const int *__restrict__ rowptr, const uint32_t *__restrict__ idx,
                                  const float *__restrict__ val, int K, int R, int S, int CC,
-                                 int KG, int NCH, int NG, int NSLOT, int PITCH, int VW,
-                                 const int *__restrict__ segptr, Rec *__restrict__ recs)
+                                 int SLOTS, int WAVES, int NCH, int NG, int IN_ROWS, int PITCH,
+                                 int BV, const int *__restrict__ segptr, Rec *__restrict__ recs)
 {
     const long long b = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long long nb = (long long)NG * NCH * KG;
+    const long long nb = (long long)NG * NCH * SLOTS * WAVES;
+    if (b < kPlanSpare) {  // spare records a prefetching reader may touch past the end
+        const int last = segptr[nb];
+        Rec z;
+        z.off = 0u;
+        z.val = 0.0f;
+        recs[last + b] = z;
+    }
     if (b >= nb) return;
-    const int kk = (int)(b % KG);
-    const int ci = (int)((b / KG) % NCH);
-    const int g = (int)(b / ((long long)KG * NCH));
-    const int k = g * KG + kk;
-    if (k >= K) return;
+    const Bucket q = decode_bucket(b, SLOTS, WAVES, NCH);
+    if (q.k >= K) return;
     const int RS = R * S;
-    const int lo = rowptr[k], hi = rowptr[k + 1];
-    const int a = lower_bound_u32(idx, lo, hi, (uint32_t)ci * CC * RS);
-    const int e = lower_bound_u32(idx, lo, hi, (uint32_t)(ci + 1) * CC * RS);
+    const int lo = rowptr[q.k], hi = rowptr[q.k + 1];
+    const int a = lower_bound_u32(idx, lo, hi, (uint32_t)q.ci * CC * RS);
+    const int e = lower_bound_u32(idx, lo, hi, (uint32_t)(q.ci + 1) * CC * RS);
     int o = segptr[b];
-    const int oend = segptr[b + 1];
     for (int i = a; i < e; ++i, ++o) {
         const uint32_t f = idx[i];
-        const int c = (int)(f / RS) - ci * CC;
+        const int c = (int)(f / RS) - q.ci * CC;
         const int rs = (int)(f % RS);
         const int r = rs / S, s = rs % S;
         Rec rec;
-        rec.off = (uint32_t)(((c * NSLOT + r) * PITCH + s) * VW * 4);
+        rec.off = (uint32_t)(((c * IN_ROWS + r) * PITCH + s) * BV * 4);
         rec.val = val[i];
-        recs[o] = rec;
-    }
-    for (; o < oend; ++o) {  // padding records (weight +0.0 at the tile origin)
-        Rec rec;
-        rec.off = 0u;
-        rec.val = 0.0f;
         recs[o] = rec;
     }
 }
@@ -244,6 +253,52 @@ __global__ void __launch_bounds__(kBlock) maxpool2x2_kernel(const float *__restr
     y[o] = m;
 }
 
+// same pooling on a batch-interleaved (N4) tensor: one thread per output pixel of one image
+// group, all four images at once
+__global__ void __launch_bounds__(kBlock) maxpool2x2_n4_kernel(const float4 *__restrict__ x,
+                                                               long long GC, int H, int W, int Ho,
+                                                               int Wo, float4 *__restrict__ y)
+{
+    const long long o = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (o >= GC * Ho * Wo) return;
+    const int ox = (int)(o % Wo);
+    const int oy = (int)((o / Wo) % Ho);
+    const long long gc = o / ((long long)Wo * Ho);
+    const float4 *p = x + (gc * H + 2 * oy) * W + 2 * ox;
+    const float4 a = p[0], b = p[1], c = p[W], d = p[W + 1];
+    auto mx4 = [](float p0, float p1, float p2, float p3) {  // same compare order as the NCHW kernel
+        float m = p0;
+        m = p1 > m ? p1 : m;
+        m = p2 > m ? p2 : m;
+        m = p3 > m ? p3 : m;
+        return m;
+    };
+    y[o] = make_float4(mx4(a.x, b.x, c.x, d.x), mx4(a.y, b.y, c.y, d.y), mx4(a.z, b.z, c.z, d.z),
+                       mx4(a.w, b.w, c.w, d.w));
+}
+
+// NCHW <-> N4 ([ceil(N/4)][C][H][W][4]); images past N read as / are written as nothing (N4 pad
+// lanes are filled with 0)
+__global__ void __launch_bounds__(kBlock) layout_convert_kernel(const float *__restrict__ src,
+                                                                int N, long long CHW, int src_n4,
+                                                                float *__restrict__ dst)
+{
+    const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
+    const long long groups = (N + 3) / 4;
+    if (t >= groups * CHW) return;
+    const long long g = t / CHW, q = t % CHW;
+    if (src_n4) {
+        const float4 v = reinterpret_cast<const float4 *>(src)[t];
+        const float e[4] = {v.x, v.y, v.z, v.w};
+        for (int b = 0; b < 4; ++b)
+            if (g * 4 + b < N) dst[(g * 4 + b) * CHW + q] = e[b];
+    } else {
+        float e[4];
+        for (int b = 0; b < 4; ++b) e[b] = g * 4 + b < N ? src[(g * 4 + b) * CHW + q] : 0.0f;
+        reinterpret_cast<float4 *>(dst)[t] = make_float4(e[0], e[1], e[2], e[3]);
+    }
+}
+
 inline unsigned blocks_for(long long n, int per) { return (unsigned)((n + per - 1) / per); }
 
 }  // namespace
@@ -267,12 +322,12 @@ hipError_t launch_filter_pack(const float *w, int K, long long row, const int *r
     return hipGetLastError();
 }
 
-hipError_t launch_plan_count(const int *rowptr, const uint32_t *idx, int K, int RS, int CC, int KG,
-                             int NCH, int NG, int pad_to, int *cnt, hipStream_t st)
+hipError_t launch_plan_count(const int *rowptr, const uint32_t *idx, int K, int RS, const SfGeom &g,
+                             int NCH, int NG, int *cnt, hipStream_t st)
 {
-    const long long nb = (long long)NG * NCH * KG;
+    const long long nb = (long long)NG * NCH * g.KG;
     hipLaunchKernelGGL(plan_count_kernel, dim3(blocks_for(nb, kBlock)), dim3(kBlock), 0, st, rowptr,
-                       idx, K, RS, CC, KG, NCH, NG, pad_to, cnt);
+                       idx, K, RS, g.CC, g.SLOTS, g.WAVES, NCH, NG, cnt);
     return hipGetLastError();
 }
 
@@ -282,7 +337,8 @@ hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float 
 {
     const long long nb = (long long)NG * NCH * g.KG;
     hipLaunchKernelGGL(plan_fill_kernel, dim3(blocks_for(nb, kBlock)), dim3(kBlock), 0, st, rowptr,
-                       idx, val, K, R, S, g.CC, g.KG, NCH, NG, g.NSLOT, g.PITCH, g.VW, segptr, recs);
+                       idx, val, K, R, S, g.CC, g.SLOTS, g.WAVES, NCH, NG, g.IN_ROWS, g.PITCH, g.BV,
+                       segptr, recs);
     return hipGetLastError();
 }
 
@@ -303,9 +359,29 @@ hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, const i
     return hipGetLastError();
 }
 
-hipError_t launch_maxpool2x2(const float *x, int N, int C, int H, int W, float *y, hipStream_t st)
+hipError_t launch_layout_convert(const float *src, int N, int C, int H, int W, int src_n4, float *dst,
+                                 hipStream_t st)
+{
+    const long long CHW = (long long)C * H * W;
+    const long long n = (long long)((N + 3) / 4) * CHW;
+    hipLaunchKernelGGL(layout_convert_kernel, dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, st, src, N,
+                       CHW, src_n4, dst);
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool2x2(const float *x, int N, int C, int H, int W, float *y, int n4,
+                             hipStream_t st)
 {
     const int Ho = H / 2, Wo = W / 2;
+    if (n4) {
+        const long long GC = (long long)((N + 3) / 4) * C;
+        const long long m = GC * Ho * Wo;
+        if (m == 0) return hipSuccess;
+        hipLaunchKernelGGL(maxpool2x2_n4_kernel, dim3(blocks_for(m, kBlock)), dim3(kBlock), 0, st,
+                           reinterpret_cast<const float4 *>(x), GC, H, W, Ho, Wo,
+                           reinterpret_cast<float4 *>(y));
+        return hipGetLastError();
+    }
     const long long n = (long long)N * C * Ho * Wo;
     if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(maxpool2x2_kernel, dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, st, x,

@@ -6,69 +6,140 @@
 // into a zero-filled border (Sec. 5, "Other layers").
 //
 // How it is mapped to gfx950 (ours, not the paper's CPU loops):
-//   * output-stationary: a work-group owns a TH x TW output tile of one image and KG output
-//     channels; each wave owns SLOTS of those channels and keeps P = VW*NV vertically
-//     adjacent outputs per lane in fp32 registers, lanes running along x (LW lanes per row)
-//     so that global loads and stores are coalesced;
-//   * the input channels are walked in chunks of CC: the chunk's input tile with its halo is
-//     staged in LDS (zero-filled outside the image);
-//   * per chunk and output channel the plan holds a contiguous run of records {LDS byte
-//     offset of tap (c,r,s), weight}; the run is wave-uniform, so it is fetched with scalar
-//     loads, and the hot loop per record is: one address add, NV LDS reads of VW words,
-//     P fused multiply-adds;
-//   * with VW > 1 the tile is stored as vectors of VW consecutive rows per (row, x) slot so
-//     that one ds_read_b64 / ds_read_b128 feeds VW outputs of a lane.
+//   * output-stationary: a work-group owns a TH x TW output tile of IMGS images and KG output
+//     channels; each wave owns SLOTS of those channels.  A lane keeps, per channel, NV
+//     vertically adjacent outputs of BV images in fp32 registers (P = NV*BV accumulators);
+//     lanes run along x (LW per row), then along LHR row groups and IG image groups, so
+//     global loads and stores are coalesced along x;
+//   * the input channels are walked in chunks of CC.  The chunk's input tile with its halo
+//     sits in LDS with the BV images of a lane interleaved per pixel
+//     ([ig][c][row][col][BV]), so one aligned ds_read_b64 / ds_read_b128 feeds BV
+//     accumulators whatever the tap shift (gfx950 reads LDS about twice as fast with
+//     b64/b128 as with b32; measured).  Staging uses buffer loads that write LDS directly
+//     (no registers, no ds_write): lane l of a load fills dword l of a 256-byte LDS line,
+//     out-of-image lanes carry an out-of-range offset and deposit 0.0.  Two LDS buffers
+//     alternate: the loads of chunk ci+1 are in flight while chunk ci is computed, and one
+//     barrier per chunk separates them;
+//   * per wave the plan holds ONE contiguous stream of records {LDS byte offset of tap
+//     (c mod CC, r, s), weight}, ordered by (chunk, channel slot).  The stream is
+//     wave-uniform: it comes through scalar loads into a small SGPR queue kept 2U-1 records
+//     ahead, and the hot loop handles U records per trip: U address adds, U*NV LDS reads,
+//     U*P fused multiply-adds.
+#include <type_traits>
+
 #include "internal.h"
 
 namespace fscnn {
 
 namespace {
 
-template <int LW_, int VW_, int NV_, int SLOTS_, int WAVES_, int CC_, int R_, int S_>
+template <int BV_, int LW_, int LHR_, int NV_, int SLOTS_, int WAVES_, int CC_, int U_, int NB_, int R_, int S_,
+          bool IN4_ = false, bool OUT4_ = false>
 struct Cfg {
-    static constexpr int LW = LW_, VW = VW_, NV = NV_, SLOTS = SLOTS_, WAVES = WAVES_, CC = CC_;
-    static constexpr int R = R_, S = S_;
-    static constexpr int LH = 64 / LW;           // lane rows per wave
-    static constexpr int P = VW * NV;            // outputs per lane (vertical)
-    static constexpr int TH = LH * P, TW = LW;   // output tile of the work-group
+    static constexpr int BV = BV_, LW = LW_, LHR = LHR_, NV = NV_, SLOTS = SLOTS_, WAVES = WAVES_;
+    static constexpr int CC = CC_, U = U_, NB = NB_, R = R_, S = S_;
+    // IN4 / OUT4: the input / output tensor is stored batch-interleaved by four ("N4":
+    // [N/4][C][H][W][4]) instead of NCHW; then a lane's four images are 16 contiguous bytes
+    static constexpr bool IN4 = IN4_, OUT4 = OUT4_;
+    static_assert((!IN4 && !OUT4) || BV == 4, "N4 tensors need four images per lane");
+    static constexpr int IG = 64 / (LW * LHR);   // image groups across the lanes of a wave
+    static_assert(IG * LW * LHR == 64, "lanes must factor as LW * LHR * IG");
+    static_assert(U == 1 || U == 2 || U == 4, "records per trip");
+    static constexpr int IMGS = BV * IG;         // images per work-group
+    static constexpr int P = NV * BV;            // accumulators per lane and channel
+    static constexpr int TH = LHR * NV, TW = LW; // output tile
     static constexpr int IN_ROWS = TH + R - 1;
-    static constexpr int NSLOT = IN_ROWS - VW + 1;  // vector slots (start rows) per channel
-    static constexpr int PITCH = TW + S - 1;        // slots per row
-    static constexpr int CH_ELEMS = NSLOT * PITCH;  // slots per channel
-    static constexpr int LDS_WORDS = CC * CH_ELEMS * VW;
+    static constexpr int PITCH = TW + S - 1;
+    static constexpr int IG_ELEMS = CC * IN_ROWS * PITCH;  // BV-vectors per image group
+    static constexpr int IG_DW = IG_ELEMS * BV;            // dwords per image group
+    // one staging load fills an LDS line of 64 dwords (NCHW input) or 64 BV-vectors (N4 input)
+    static constexpr int LINE_BYTES = IN4 ? 1024 : 256;
+    static constexpr int NI = IN4 ? (IG_ELEMS + 63) / 64 : (IG_DW + 63) / 64;  // lines per image group
+    static constexpr int IG_BYTES = NI * LINE_BYTES;       // padded so that a line never spills
+    static constexpr int BUF_BYTES = IG * IG_BYTES;
+    static constexpr int LDS_BYTES = NB * BUF_BYTES;
+    static constexpr int D = NB - 1;                       // chunks whose loads run ahead
+    static_assert(NB >= 2, "at least the chunk being read and the one being loaded");
     static constexpr int KG = SLOTS * WAVES;
     static constexpr int NT = WAVES * 64;
-    static constexpr int VSTEP_BYTES = VW * PITCH * VW * 4;  // +VW rows, in bytes
+    static constexpr int NIW = (NI + WAVES - 1) / WAVES;   // lines per wave and image group
+    static constexpr int ROWSTEP = PITCH * BV * 4;         // bytes from one tile row to the next
+    static constexpr int FIFO = 2 * U - 1;                 // records held ahead in SGPRs
+    // loads a wave may leave in flight once the NEXT chunk has to be complete: every wave
+    // issues at least IG*(NI/WAVES) lines per chunk, and D-1 younger chunks follow it
+    static constexpr int WAITN = (D - 1) * IG * (NI / WAVES) > 63 ? 63 : (D - 1) * IG * (NI / WAVES);
 };
 
-template <int VW> struct VecT;
+// s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt is split over
+// bits 3:0 and 15:14; expcnt and lgkmcnt fields are left at "no wait")
+template <int N> __device__ inline void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
+
+constexpr int kInvalidOff = 0x7ffffff0;  // beyond any num_records: the buffer load returns 0
+static_assert(kPlanSpare >= 2 * 4 - 1 + 4, "queue depth plus one step must stay inside the spare records");
+
+template <int BV> struct VecT;
 template <> struct VecT<1> { using T = float; };
 template <> struct VecT<2> { using T = float2; };
 template <> struct VecT<4> { using T = float4; };
 
-template <int VW> __device__ inline float vec_get(const typename VecT<VW>::T &v, int e);
-template <> __device__ inline float vec_get<1>(const float &v, int) { return v; }
-template <> __device__ inline float vec_get<2>(const float2 &v, int e) { return e == 0 ? v.x : v.y; }
-template <> __device__ inline float vec_get<4>(const float4 &v, int e)
+template <int BV> __device__ inline float vget(const typename VecT<BV>::T &v, int e);
+template <> __device__ inline float vget<1>(const float &v, int) { return v; }
+template <> __device__ inline float vget<2>(const float2 &v, int e) { return e == 0 ? v.x : v.y; }
+template <> __device__ inline float vget<4>(const float4 &v, int e)
 {
     return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
+}
+
+typedef int int4v __attribute__((ext_vector_type(4)));
+
+// One buffer load that writes LDS directly (MUBUF with LDS=1): lane l deposits the dword it
+// loads at LDS byte address lds_addr + 4*l; a lane whose offset is out of the descriptor's
+// range deposits 0.0.  Written as inline assembly on purpose: the compiler does not count it
+// as an LDS store, so it puts no vmcnt wait in front of later LDS reads of the OTHER buffer.
+// The caller waits (vmcnt(0), then a barrier) before anyone reads what was loaded.
+__device__ inline void lds_dma_dwordx4(int4v rsrc, uint32_t lds_addr, int voff)
+{
+    // same, 16 bytes per lane: lane l deposits its four dwords at lds_addr + 16*l
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "memory", "m0");
+}
+__device__ inline void lds_dma_dword(int4v rsrc, uint32_t lds_addr, int voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "memory", "m0");
+}
+
+// Work-groups are dealt round-robin to the 8 XCDs; renumber them so that consecutive logical
+// ids (the channel groups of one input tile) land on the same XCD and share its L2.
+__device__ inline int xcd_remap(int bid, int nblk)
+{
+    const int q = nblk >> 3, rem = nblk & 7;
+    const int xcd = bid & 7, slot = bid >> 3;
+    return xcd < rem ? xcd * (q + 1) + slot : rem * (q + 1) + (xcd - rem) * q + slot;
 }
 
 template <class G>
 __global__ void __launch_bounds__(G::NT)
 conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                      const float *__restrict__ bias, const Rec *__restrict__ recs,
-                     const int *__restrict__ segptr, int C, int H, int W, int K, int Ho, int Wo,
-                     int ph, int pw, int relu, int NCH, int NG, int tiles_x, int tiles_per_img)
+                     const int *__restrict__ segptr, int N, int C, int H, int W, int K, int Ho,
+                     int Wo, int ph, int pw, int relu, int NCH, int NG, int tiles_x,
+                     int tiles_per_img, int nblk)
 {
-    using V = typename VecT<G::VW>::T;
-    extern __shared__ __align__(16) float lds[];
+    using V = typename VecT<G::BV>::T;
+    extern __shared__ __align__(256) char ldsb[];
 
-    // work-group -> (channel group, spatial tile, image); groups of one tile are adjacent
-    const int bid = blockIdx.x;
-    const int kg = bid % NG;
-    const int t = (bid / NG) % tiles_per_img;
-    const int n = bid / (NG * tiles_per_img);
+    const int lid = xcd_remap(blockIdx.x, nblk);
+    const int kg = lid % NG;
+    const int t = (lid / NG) % tiles_per_img;
+    const int n0 = (lid / (NG * tiles_per_img)) * G::IMGS;
     const int ty0 = (t / tiles_x) * G::TH;
     const int tx0 = (t % tiles_x) * G::TW;
 
@@ -76,8 +147,55 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lx = lane % G::LW;
-    const int row0 = (lane / G::LW) * G::P;  // first output row of this lane inside the tile
-    const uint32_t lane_base = (uint32_t)((row0 * G::PITCH + lx) * G::VW * 4);
+    const int lh = (lane / G::LW) % G::LHR;
+    const int ig = lane / (G::LW * G::LHR);
+    const uint32_t lane_base = (uint32_t)(ig * G::IG_BYTES + ((lh * G::NV) * G::PITCH + lx) * G::BV * 4);
+
+    // ---- staging table (A4): for each LDS line this wave fills, the global byte offset of the
+    // float that lands in this lane's dword, relative to channel ci*CC of the group's first
+    // image.  The same table serves every chunk and image group.
+    const int HW = H * W;
+    int goff[G::NIW];
+#pragma unroll
+    for (int q = 0; q < G::NIW; ++q) {
+        const int d = (wave + q * G::WAVES) * 64 + lane;  // dword (NCHW) or vector (N4) of the region
+        const int e = G::IN4 ? d : d / G::BV, b = G::IN4 ? 0 : d % G::BV;
+        const int cl = e / (G::IN_ROWS * G::PITCH);
+        const int rem = e % (G::IN_ROWS * G::PITCH);
+        const int gy = ty0 - ph + rem / G::PITCH;
+        const int gx = tx0 - pw + rem % G::PITCH;
+        const bool ok = e < G::IG_ELEMS && gy >= 0 && gy < H && gx >= 0 && gx < W;
+        const int pix = cl * HW + gy * W + gx;
+        goff[q] = !ok ? kInvalidOff : G::IN4 ? pix * 16 : (b * C * HW + pix) * 4;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ldsb;
+    auto fetch = [&](int ci, int buf) {
+        const int crem = C - ci * G::CC;  // channels left from this chunk on (> 0)
+#pragma unroll
+        for (int g = 0; g < G::IG; ++g) {
+            const int n = n0 + g * G::BV;
+            int nvalid = N - n;
+            nvalid = nvalid > G::BV ? G::BV : nvalid;
+            // NCHW: the group's first image from channel ci*CC on, up to the end of its last
+            // valid image; N4: the group's block from channel ci*CC on
+            const long long first = G::IN4 ? ((long long)(n / 4) * C + (long long)ci * G::CC) * HW * 4
+                                           : ((long long)n * C + (long long)ci * G::CC) * HW;
+            const uint64_t base = (uint64_t)(nvalid > 0 ? x + first : x);
+            const int nbytes = nvalid <= 0 ? 0 : G::IN4 ? crem * HW * 16 : ((nvalid - 1) * C + crem) * HW * 4;
+            // raw buffer descriptor: 48-bit base, stride 0, num_records in bytes, 32-bit data
+            const int4v rs = {(int)(uint32_t)base, (int)((base >> 32) & 0xffffu), nbytes, 0x00020000};
+#pragma unroll
+            for (int q = 0; q < G::NIW; ++q) {
+                const int line = wave + q * G::WAVES;
+                const uint32_t dst =
+                    lds0 + (uint32_t)(buf * G::BUF_BYTES + g * G::IG_BYTES + line * G::LINE_BYTES);
+                if (line < G::NI) {
+                    if constexpr (G::IN4) lds_dma_dwordx4(rs, dst, goff[q]);
+                    else lds_dma_dword(rs, dst, goff[q]);
+                }
+            }
+        }
+    };
 
     float acc[G::SLOTS][G::P];
 #pragma unroll
@@ -85,75 +203,123 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
 #pragma unroll
         for (int p = 0; p < G::P; ++p) acc[j][p] = 0.0f;
 
-    const float *xn = x + (long long)n * C * H * W;
-    const char *ldsb = reinterpret_cast<const char *>(lds);
-
-    for (int ci = 0; ci < NCH; ++ci) {
-        if (ci) __syncthreads();  // everyone is done reading the previous chunk
-        // ---- stage the chunk's input tile (A4): slot (c, q, col) holds rows q .. q+VW-1
-        for (int e = tid; e < G::CC * G::CH_ELEMS; e += G::NT) {
-            const int cl = e / G::CH_ELEMS;
-            const int rem = e % G::CH_ELEMS;
-            const int q = rem / G::PITCH;
-            const int col = rem % G::PITCH;
-            const int c = ci * G::CC + cl;
-            const int gx = tx0 - pw + col;
-            float tmp[G::VW];
+    // this wave's record stream, its (chunk, slot) boundaries, and the SGPR queue of records
+    const int *seg = segptr + (long long)(kg * G::WAVES + wave) * NCH * G::SLOTS;
+    int i = seg[0];
+    Rec q[G::FIFO];
 #pragma unroll
-            for (int v = 0; v < G::VW; ++v) {
-                const int gy = ty0 - ph + q + v;
-                float val = 0.0f;
-                if (c < C && gy >= 0 && gy < H && gx >= 0 && gx < W)
-                    val = xn[((long long)c * H + gy) * W + gx];
-                tmp[v] = val;
-            }
-            if constexpr (G::VW == 1) {
-                lds[e] = tmp[0];
-            } else if constexpr (G::VW == 2) {
-                reinterpret_cast<float2 *>(lds)[e] = make_float2(tmp[0], tmp[1]);
-            } else {
-                reinterpret_cast<float4 *>(lds)[e] = make_float4(tmp[0], tmp[1], tmp[2], tmp[3]);
-            }
+    for (int f = 0; f < G::FIFO; ++f) q[f] = recs[i + f];
+    int bnd[G::SLOTS];
+#pragma unroll
+    for (int j = 0; j < G::SLOTS; ++j) bnd[j] = seg[j + 1];
+
+    // the first D chunks start loading; chunk 0 must have landed before anyone reads it
+#pragma unroll
+    for (int d = 0; d < G::D; ++d)
+        if (d < NCH) fetch(d, d);
+    if (G::D <= NCH) wait_vmcnt<G::WAITN>(); else wait_vmcnt<0>();
+    __syncthreads();
+
+    int rbuf = 0;         // ring slot of the chunk being computed
+    int wbuf = G::D;      // ring slot the next load goes to (last read one chunk ago)
+    for (int ci = 0; ci < NCH; ++ci) {
+        int nbnd[G::SLOTS];
+        if (ci + G::D < NCH) fetch(ci + G::D, wbuf);  // in flight while D chunks are computed
+        wbuf = wbuf + 1 == G::NB ? 0 : wbuf + 1;
+        if (ci + 1 < NCH) {
+#pragma unroll
+            for (int j = 0; j < G::SLOTS; ++j) nbnd[j] = seg[(ci + 1) * G::SLOTS + j + 1];
+        } else {
+#pragma unroll
+            for (int j = 0; j < G::SLOTS; ++j) nbnd[j] = bnd[G::SLOTS - 1];
         }
-        __syncthreads();
+        const char *tile = ldsb + (lane_base + (uint32_t)(rbuf * G::BUF_BYTES));
+        rbuf = rbuf + 1 == G::NB ? 0 : rbuf + 1;
 
         // ---- gather-FMA over this wave's records of the chunk (A5)
-        const int *sp = segptr + ((long long)(kg * NCH + ci) * G::KG + wave * G::SLOTS);
-        int bnd[G::SLOTS + 1];
-#pragma unroll
-        for (int j = 0; j <= G::SLOTS; ++j) bnd[j] = sp[j];
 #pragma unroll
         for (int j = 0; j < G::SLOTS; ++j) {
-            for (int i = bnd[j]; i < bnd[j + 1]; ++i) {
-                const Rec rc = recs[i];
-                const char *p = ldsb + (lane_base + rc.off);
+            const int end = bnd[j];
+            // M records per step: read their taps, multiply-add, then advance the queue by M
+            auto step = [&](auto mtag) {
+                constexpr int M = decltype(mtag)::value;
+                V in[M][G::NV];
 #pragma unroll
-                for (int v = 0; v < G::NV; ++v) {
-                    const V in = *reinterpret_cast<const V *>(p + v * G::VSTEP_BYTES);
+                for (int m = 0; m < M; ++m) {
+                    const char *p = tile + q[m].off;
 #pragma unroll
-                    for (int e = 0; e < G::VW; ++e)
-                        acc[j][v * G::VW + e] =
-                            __builtin_fmaf(rc.val, vec_get<G::VW>(in, e), acc[j][v * G::VW + e]);
+                    for (int v = 0; v < G::NV; ++v)
+                        in[m][v] = *reinterpret_cast<const V *>(p + v * G::ROWSTEP);
                 }
-            }
+                Rec fresh[M];
+#pragma unroll
+                for (int m = 0; m < M; ++m) fresh[m] = recs[i + G::FIFO + m];
+#pragma unroll
+                for (int m = 0; m < M; ++m)
+#pragma unroll
+                    for (int v = 0; v < G::NV; ++v)
+#pragma unroll
+                        for (int b = 0; b < G::BV; ++b)
+                            acc[j][v * G::BV + b] = __builtin_fmaf(
+                                q[m].val, vget<G::BV>(in[m][v], b), acc[j][v * G::BV + b]);
+#pragma unroll
+                for (int f = 0; f + M < G::FIFO; ++f) q[f] = q[f + M];
+#pragma unroll
+                for (int m = 0; m < M; ++m) q[G::FIFO - M + m] = fresh[m];
+                i += M;
+            };
+            while (end - i >= G::U) step(std::integral_constant<int, G::U>());
+            if constexpr (G::U >= 4)
+                if (end - i >= 2) step(std::integral_constant<int, 2>());
+            if constexpr (G::U >= 2)
+                if (end - i >= 1) step(std::integral_constant<int, 1>());
+            i = end;  // boundaries never decrease, so the steps above always end exactly here
         }
+#pragma unroll
+        for (int j = 0; j < G::SLOTS; ++j) bnd[j] = nbnd[j];
+        // the next chunk's lines of this wave must be in LDS before the barrier lets anyone read
+        if (ci + G::D < NCH) wait_vmcnt<G::WAITN>(); else wait_vmcnt<0>();
+        __syncthreads();
     }
 
-    // ---- epilogue (A6): bias, ReLU, coalesced NCHW store
+    // ---- epilogue (A6): bias, ReLU, store (coalesced along x)
     const int ox = tx0 + lx;
+    const long long plane = (long long)Ho * Wo;
 #pragma unroll
     for (int j = 0; j < G::SLOTS; ++j) {
         const int k = kg * G::KG + wave * G::SLOTS + j;
         if (k >= K) break;
-        const float b = bias ? bias[k] : 0.0f;
-        float *yk = y + ((long long)n * K + k) * Ho * Wo;
+        const float bk = bias ? bias[k] : 0.0f;
+        if constexpr (G::OUT4) {
+            const int n = n0 + ig * 4;  // first image of this lane's group
+            float4 *yk = reinterpret_cast<float4 *>(y) + ((long long)(n / 4) * K + k) * plane;
 #pragma unroll
-        for (int p = 0; p < G::P; ++p) {
-            const int oy = ty0 + row0 + p;
-            if (oy < Ho && ox < Wo) {
-                float v = acc[j][p] + b;
-                if (relu) v = v > 0.0f ? v : 0.0f;
-                yk[(long long)oy * Wo + ox] = v;
+            for (int v = 0; v < G::NV; ++v) {
+                const int oy = ty0 + lh * G::NV + v;
+                if (n < N && oy < Ho && ox < Wo) {
+                    float r[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        r[b] = acc[j][v * 4 + b] + bk;
+                        if (relu) r[b] = r[b] > 0.0f ? r[b] : 0.0f;
+                    }
+                    yk[(long long)oy * Wo + ox] = make_float4(r[0], r[1], r[2], r[3]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < G::BV; ++b) {
+                const int n = n0 + ig * G::BV + b;
+                float *yk = y + ((long long)n * K + k) * plane;
+#pragma unroll
+                for (int v = 0; v < G::NV; ++v) {
+                    const int oy = ty0 + lh * G::NV + v;
+                    if (n < N && oy < Ho && ox < Wo) {
+                        float r = acc[j][v * G::BV + b] + bk;
+                        if (relu) r = r > 0.0f ? r : 0.0f;
+                        yk[(long long)oy * Wo + ox] = r;
+                    }
+                }
             }
         }
     }
@@ -204,57 +370,73 @@ hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, in
                         int Wo, int ph, int pw, const float *bias, int relu, float *y,
                         hipStream_t st)
 {
-    constexpr int lds_bytes = G::LDS_WORDS * 4;
-    static_assert(lds_bytes <= 160 * 1024, "tile exceeds the 160 KB LDS of a gfx950 compute unit");
-    if (lds_bytes > 64 * 1024) {
+    static_assert(G::LDS_BYTES <= 160 * 1024, "tile exceeds the 160 KB LDS of a gfx950 CU");
+    if (G::LDS_BYTES > 64 * 1024) {
         static hipError_t attr = hipFuncSetAttribute(
             reinterpret_cast<const void *>(&conv_sf_tiled_kernel<G>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
         if (attr != hipSuccess) return attr;
     }
     const int tiles_x = (Wo + G::TW - 1) / G::TW;
     const int tiles_y = (Ho + G::TH - 1) / G::TH;
-    const long long nblk = (long long)p.NG * tiles_x * tiles_y * N;
+    const int nbat = (N + G::IMGS - 1) / G::IMGS;
+    const long long nblk = (long long)p.NG * tiles_x * tiles_y * nbat;
     if (nblk <= 0 || nblk > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(conv_sf_tiled_kernel<G>, dim3((unsigned)nblk), dim3(G::NT), lds_bytes, st, x,
-                       y, bias, p.recs, p.segptr, C, H, W, K, Ho, Wo, ph, pw, relu, p.NCH, p.NG,
-                       tiles_x, tiles_x * tiles_y);
+    hipLaunchKernelGGL(conv_sf_tiled_kernel<G>, dim3((unsigned)nblk), dim3(G::NT), G::LDS_BYTES, st,
+                       x, y, bias, p.recs, p.segptr, N, C, H, W, K, Ho, Wo, ph, pw, relu, p.NCH,
+                       p.NG, tiles_x, tiles_x * tiles_y, (int)nblk);
     return hipGetLastError();
 }
 
 template <class G> SfGeom geom_of()
 {
     SfGeom g;
-    g.LW = G::LW; g.VW = G::VW; g.NV = G::NV; g.SLOTS = G::SLOTS; g.WAVES = G::WAVES; g.CC = G::CC;
-    g.R = G::R; g.S = G::S; g.TH = G::TH; g.TW = G::TW; g.NSLOT = G::NSLOT; g.PITCH = G::PITCH;
-    g.KG = G::KG; g.lds_bytes = G::LDS_WORDS * 4; g.pad_to = 1;
+    g.BV = G::BV; g.LW = G::LW; g.LHR = G::LHR; g.NV = G::NV; g.SLOTS = G::SLOTS;
+    g.WAVES = G::WAVES; g.CC = G::CC; g.R = G::R; g.S = G::S; g.TH = G::TH; g.TW = G::TW;
+    g.IMGS = G::IMGS; g.IN_ROWS = G::IN_ROWS; g.PITCH = G::PITCH; g.KG = G::KG;
+    g.lds_bytes = G::LDS_BYTES;
     return g;
 }
 
 struct Variant {
     const char *name;
     SfGeom g;
-    LaunchFn fn;
+    LaunchFn fn[2][2];  // [input is N4][output is N4]; null where the configuration has no such form
 };
 
-#define FSCNN_V(LW, VW, NV, SLOTS, WAVES, CC)                                                  \
-    {"lw" #LW "_vw" #VW "_nv" #NV "_s" #SLOTS "_w" #WAVES "_cc" #CC,                        \
-     geom_of<Cfg<LW, VW, NV, SLOTS, WAVES, CC, 3, 3>>(),                                      \
-     &launch_tiled<Cfg<LW, VW, NV, SLOTS, WAVES, CC, 3, 3>>}
+#define FSCNN_CFG(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, I4, O4) \
+    Cfg<BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, 3, 3, I4, O4>
+#define FSCNN_NAME(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB) \
+    "bv" #BV "_lw" #LW "x" #LHR "_nv" #NV "_s" #SLOTS "_w" #WAVES "_cc" #CC "_u" #U "_nb" #NB
+// four images per lane: all four layout combinations
+#define FSCNN_V4(LW, LHR, NV, SLOTS, WAVES, CC, U, NB)                                        \
+    {FSCNN_NAME(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB),                                     \
+     geom_of<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>(),             \
+     {{&launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>,       \
+       &launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, true)>},       \
+      {&launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, false)>,        \
+       &launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, true)>}}}
+// one or two images per lane: NCHW only
+#define FSCNN_V(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB)                                     \
+    {FSCNN_NAME(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB),                                    \
+     geom_of<FSCNN_CFG(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>(),            \
+     {{&launch_tiled<FSCNN_CFG(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>, nullptr}, \
+      {nullptr, nullptr}}}
 
 const Variant *variants(int *count)
 {
     static const Variant table[] = {
-        FSCNN_V(64, 1, 8, 8, 4, 16),   //  1
-        FSCNN_V(64, 1, 8, 8, 8, 16),   //  2
-        FSCNN_V(64, 1, 4, 8, 4, 16),   //  3
-        FSCNN_V(64, 2, 4, 8, 4, 8),    //  4
-        FSCNN_V(64, 4, 2, 8, 4, 8),    //  5
-        FSCNN_V(32, 1, 8, 8, 4, 16),   //  6
-        FSCNN_V(32, 4, 2, 8, 4, 8),    //  7
-        FSCNN_V(16, 1, 4, 8, 4, 16),   //  8
-        FSCNN_V(16, 4, 1, 8, 4, 8),    //  9
-        FSCNN_V(64, 1, 8, 16, 4, 16),  // 10
+        FSCNN_V4(64, 1, 4, 4, 8, 4, 1, 3),    //  1
+        FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),   //  2
+        FSCNN_V4(64, 1, 4, 8, 8, 8, 1, 3),    //  3
+        FSCNN_V4(64, 1, 4, 4, 8, 8, 1, 2),    //  4
+        FSCNN_V4(32, 1, 4, 4, 8, 4, 1, 3),    //  5
+        FSCNN_V4(32, 1, 4, 4, 16, 8, 1, 3),   //  6
+        FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),    //  7
+        FSCNN_V4(16, 1, 2, 4, 4, 8, 1, 3),    //  8
+        FSCNN_V(1, 64, 1, 8, 8, 8, 8, 1, 2),  //  9
+        FSCNN_V(1, 32, 2, 8, 8, 8, 8, 1, 2),  // 10
+        FSCNN_V(1, 16, 4, 4, 8, 8, 8, 1, 2),  // 11
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
@@ -287,24 +469,34 @@ bool sf_variant_geom(int variant, int R, int S, SfGeom *g)
     return true;
 }
 
-// Automatic choice: lanes-per-row follows the output width so that few lanes idle.
+bool sf_variant_has_layout(int variant, int in4, int out4)
+{
+    int n;
+    const Variant *t = variants(&n);
+    if (variant < 1 || variant > n) return false;
+    return t[variant - 1].fn[in4 ? 1 : 0][out4 ? 1 : 0] != nullptr;
+}
+
+// Automatic choice: lanes-per-row follows the output width so that few lanes idle; batches of
+// at least four images use the image-interleaved (b128) configurations.
 int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S)
 {
-    (void)N; (void)C; (void)K; (void)H;
+    (void)C; (void)K; (void)H;
     if (R != 3 || S != 3) return 0;
-    if (W > 32) return 1;
-    if (W > 16) return 6;
-    return 8;
+    if (N >= 4) return W > 32 ? 1 : W > 16 ? 5 : 7;
+    return W > 32 ? 9 : W > 16 ? 10 : 11;
 }
 
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
-                                float *y, hipStream_t st)
+                                float *y, int in4, int out4, hipStream_t st)
 {
     int n;
     const Variant *t = variants(&n);
     if (p.variant < 1 || p.variant > n) return hipErrorInvalidValue;
-    return t[p.variant - 1].fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, st);
+    LaunchFn fn = t[p.variant - 1].fn[in4 ? 1 : 0][out4 ? 1 : 0];
+    if (!fn) return hipErrorInvalidValue;
+    return fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, st);
 }
 
 hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const float *val,
@@ -314,9 +506,8 @@ hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const f
 {
     const long long nblk = (long long)((Wo + 63) / 64) * ((Ho + 3) / 4) * N * K;
     if (nblk <= 0 || nblk > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(conv_sf_direct_kernel, dim3((unsigned)nblk), dim3(256), 0,
-                       st, rowptr, idx, val, x, N, C, H, W, K, R, S, Ho, Wo, sh, sw, ph, pw, bias,
-                       relu, y);
+    hipLaunchKernelGGL(conv_sf_direct_kernel, dim3((unsigned)nblk), dim3(256), 0, st, rowptr, idx,
+                       val, x, N, C, H, W, K, R, S, Ho, Wo, sh, sw, ph, pw, bias, relu, y);
     return hipGetLastError();
 }
 

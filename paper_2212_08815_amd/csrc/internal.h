@@ -24,23 +24,24 @@ struct Rec {
 
 // Geometry of one kernel configuration of the tiled sparse-filter convolution.
 struct SfGeom {
-    int LW, VW, NV, SLOTS, WAVES, CC;  // template parameters
-    int R, S;                          // filter extent the instance is built for
-    int TH, TW;                        // output tile
-    int NSLOT, PITCH;                  // LDS rows (vector slots) per channel, elements per row
-    int KG;                            // output channels per work-group
+    int BV, LW, LHR, NV, SLOTS, WAVES, CC;  // template parameters
+    int R, S;                               // filter extent the instance is built for
+    int TH, TW, IMGS;                       // output tile and images per work-group
+    int IN_ROWS, PITCH;                     // LDS rows per channel, BV-vectors per row
+    int KG;                                 // output channels per work-group
     int lds_bytes;
-    int pad_to;                        // records per segment are padded to a multiple of this
 };
+
+constexpr int kPlanSpare = 12;  // zero records appended to a plan's stream (reader prefetch)
 
 struct SfPlan {
     int variant = 0;   // 1-based index into the variant table
     bool direct = false;
     SfGeom g{};
     int NCH = 0, NG = 0;
-    long long nrec = 0;       // records written (including padding records)
-    int *segptr = nullptr;    // [NG*NCH*KG + 1]
-    Rec *recs = nullptr;      // [nrec]
+    long long nrec = 0;       // records (= nonzeros); the array carries kPlanSpare spare entries
+    int *segptr = nullptr;    // [NG*NCH*KG + 1], bucket order (group, wave, chunk, slot)
+    Rec *recs = nullptr;      // [nrec + kPlanSpare]
 };
 
 struct SiGeom {
@@ -80,24 +81,28 @@ hipError_t launch_filter_count(const float *w, int K, long long row, int *cnt, h
 hipError_t launch_exclusive_scan(const int *in, int *out, long long n, hipStream_t st);
 hipError_t launch_filter_pack(const float *w, int K, long long row, const int *rowptr,
                               uint32_t *idx, float *val, hipStream_t st);
-hipError_t launch_plan_count(const int *rowptr, const uint32_t *idx, int K, int RS, int CC, int KG,
-                             int NCH, int NG, int pad_to, int *cnt, hipStream_t st);
+hipError_t launch_plan_count(const int *rowptr, const uint32_t *idx, int K, int RS, const SfGeom &g,
+                             int NCH, int NG, int *cnt, hipStream_t st);
 hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float *val, int K, int R,
                             int S, const SfGeom &g, int NCH, int NG, const int *segptr, Rec *recs,
                             hipStream_t st);
 hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int *cnt, hipStream_t st);
 hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, const int *prow, int CC,
                              int NCH, uint32_t *cidx, float *xval, int *cptr, hipStream_t st);
-hipError_t launch_maxpool2x2(const float *x, int N, int C, int H, int W, float *y, hipStream_t st);
+hipError_t launch_maxpool2x2(const float *x, int N, int C, int H, int W, float *y, int n4,
+                             hipStream_t st);
+hipError_t launch_layout_convert(const float *src, int N, int C, int H, int W, int src_n4, float *dst,
+                                 hipStream_t st);
 
 // ---- conv_sf.hip
 int sf_variant_count();
 const char *sf_variant_name(int variant);
 bool sf_variant_geom(int variant, int R, int S, SfGeom *g);  // false if the variant cannot serve RxS
 int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S);
+bool sf_variant_has_layout(int variant, int in4, int out4);
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
-                                float *y, hipStream_t st);
+                                float *y, int in4, int out4, hipStream_t st);
 hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const float *val,
                                  const float *x, int N, int C, int H, int W, int K, int R, int S,
                                  int Ho, int Wo, int sh, int sw, int ph, int pw, const float *bias,

@@ -26,8 +26,11 @@ EXPORTS = [
     "fscnn_filter_destroy", "fscnn_sf_variant_count", "fscnn_sf_variant_name",
     "fscnn_conv2d_sparse_filter", "fscnn_conv2d_sparse_filter_v", "fscnn_input_compress",
     "fscnn_input_info", "fscnn_input_export", "fscnn_input_destroy", "fscnn_conv2d_sparse_input",
-    "fscnn_maxpool2x2",
+    "fscnn_maxpool2x2", "fscnn_conv2d_sparse_filter_ex", "fscnn_layout_convert",
+    "fscnn_maxpool2x2_ex",
 ]
+
+NCHW, N4 = 0, 1      # fscnn_layout_t
 
 
 class FscnnError(RuntimeError):
@@ -162,8 +165,9 @@ def filter_plan_export(f, N, H, W, stride=(1, 1), pad=(0, 0), variant=0):
     _check(lib().fscnn_filter_plan_export(*args, params.ctypes.data_as(ctypes.c_void_p), None, None, None),
            "fscnn_filter_plan_export")
     out = dict(variant=int(params[0]), CC=int(params[1]), KG=int(params[2]), NCH=int(params[3]),
-               NG=int(params[4]), NSLOT=int(params[5]), PITCH=int(params[6]), VW=int(params[7]),
-               nrec=int(params[8]), direct=bool(params[9]))
+               NG=int(params[4]), IN_ROWS=int(params[5]), PITCH=int(params[6]), BV=int(params[7]),
+               nrec=int(params[8]), direct=bool(params[9]), SLOTS=int(params[10]),
+               WAVES=int(params[11]))
     if out["direct"]:
         return out
     nb = out["NG"] * out["NCH"] * out["KG"]
@@ -179,27 +183,59 @@ def filter_plan_export(f, N, H, W, stride=(1, 1), pad=(0, 0), variant=0):
     return out
 
 
-def conv2d_sparse_filter(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=False, out=None, variant=0):
-    """fscnn_conv2d_sparse_filter(_v): x N x C x H x W -> y N x K x Ho x Wo (both CUDA float32)."""
+def n4_shape(N, C, H, W):
+    """Shape of the torch tensor that backs an N4 tensor of N images."""
+    return ((N + 3) // 4, C, H, W, 4)
+
+
+def _logical_shape(x, layout, n):
+    if layout == NCHW:
+        if x.dim() != 4:
+            raise TypeError("an NCHW tensor must be N x C x H x W")
+        return tuple(x.shape)
+    if x.dim() != 5 or x.shape[4] != 4:
+        raise TypeError("an N4 tensor must be ceil(N/4) x C x H x W x 4")
+    n = x.shape[0] * 4 if n is None else n
+    if (n + 3) // 4 != x.shape[0]:
+        raise TypeError("n does not match the N4 tensor")
+    return (n, x.shape[1], x.shape[2], x.shape[3])
+
+
+def conv2d_sparse_filter(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=False, out=None, variant=0,
+                         x_layout=NCHW, y_layout=NCHW, n=None):
+    """fscnn_conv2d_sparse_filter_ex: x -> y (CUDA float32).  NCHW tensors are N x C x H x W;
+    N4 tensors are ceil(N/4) x C x H x W x 4 with `n` the number of real images."""
     x = _dev_f32(x, "x")
     bias = _dev_f32(bias, "bias")
-    if x.dim() != 4:
-        raise TypeError("x must be N x C x H x W")
-    N, C, H, W = x.shape
+    N, C, H, W = _logical_shape(x, x_layout, n)
     K, _, R, S = f.shape
     Ho, Wo = conv2d_out_shape(H, W, R, S, stride, pad)
+    oshape = (N, K, Ho, Wo) if y_layout == NCHW else n4_shape(N, K, Ho, Wo)
     if out is None:
-        out = torch.empty((N, K, Ho, Wo), dtype=torch.float32, device=x.device)
+        out = torch.empty(oshape, dtype=torch.float32, device=x.device)
     else:
         _dev_f32(out, "out")
-        if tuple(out.shape) != (N, K, Ho, Wo):
+        if tuple(out.shape) != oshape:
             raise TypeError("out has the wrong shape")
     if bias is not None and bias.numel() != K:
         raise TypeError("bias must have K entries")
-    _check(lib().fscnn_conv2d_sparse_filter_v(f.handle, _ptr(x), _i(N), _i(C), _i(H), _i(W),
-                                              _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]),
-                                              _ptr(bias), _i(bool(relu)), _ptr(out), _i(variant),
-                                              _stream()), "fscnn_conv2d_sparse_filter")
+    _check(lib().fscnn_conv2d_sparse_filter_ex(f.handle, _ptr(x), _i(N), _i(C), _i(H), _i(W),
+                                               _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]),
+                                               _ptr(bias), _i(bool(relu)), _ptr(out), _i(x_layout),
+                                               _i(y_layout), _i(variant), _stream()),
+           "fscnn_conv2d_sparse_filter_ex")
+    return out
+
+
+def layout_convert(x, src_layout, n=None):
+    """fscnn_layout_convert: NCHW -> N4 or N4 -> NCHW (new tensor)."""
+    x = _dev_f32(x, "x")
+    N, C, H, W = _logical_shape(x, src_layout, n)
+    dst_layout = N4 if src_layout == NCHW else NCHW
+    out = torch.empty((N, C, H, W) if dst_layout == NCHW else n4_shape(N, C, H, W),
+                      dtype=torch.float32, device=x.device)
+    _check(lib().fscnn_layout_convert(_ptr(x), _i(N), _i(C), _i(H), _i(W), _i(src_layout), _ptr(out),
+                                      _i(dst_layout), _stream()), "fscnn_layout_convert")
     return out
 
 
@@ -273,11 +309,12 @@ def conv2d_sparse_input(s, w, stride=(1, 1), pad=(0, 0), bias=None, relu=False, 
     return out
 
 
-def maxpool2x2(x, out=None):
+def maxpool2x2(x, out=None, layout=NCHW, n=None):
     x = _dev_f32(x, "x")
-    N, C, H, W = x.shape
+    N, C, H, W = _logical_shape(x, layout, n)
+    oshape = (N, C, H // 2, W // 2) if layout == NCHW else n4_shape(N, C, H // 2, W // 2)
     if out is None:
-        out = torch.empty((N, C, H // 2, W // 2), dtype=torch.float32, device=x.device)
-    _check(lib().fscnn_maxpool2x2(_ptr(x), _i(N), _i(C), _i(H), _i(W), _ptr(out), _stream()),
-           "fscnn_maxpool2x2")
+        out = torch.empty(oshape, dtype=torch.float32, device=x.device)
+    _check(lib().fscnn_maxpool2x2_ex(_ptr(x), _i(N), _i(C), _i(H), _i(W), _ptr(out), _i(layout),
+                                     _stream()), "fscnn_maxpool2x2_ex")
     return out

@@ -92,32 +92,35 @@ def test_plan_regroup_decodes_to_the_canonical_rows(F):
     for v in tiled_variants(F):
         p = F.filter_plan_export(f, 1, 30, 30, (1, 1), (1, 1), variant=v)
         assert not p["direct"] and p["variant"] == v
-        CC, KG, NCH, NG = p["CC"], p["KG"], p["NCH"], p["NG"]
-        assert NCH == -(-C // CC) and NG == -(-K // KG)
+        CC, KG, NCH, NG, SL, WV = p["CC"], p["KG"], p["NCH"], p["NG"], p["SLOTS"], p["WAVES"]
+        assert NCH == -(-C // CC) and NG == -(-K // KG) and KG == SL * WV
         seg = p["segptr"]
-        assert seg[0] == 0 and np.all(np.diff(seg) >= 0) and seg[-1] == orp[-1]
-        q = p["rec_off"].astype(np.int64) // (4 * p["VW"])
-        assert np.all(p["rec_off"] % (4 * p["VW"]) == 0)
+        assert seg[0] == 0 and np.all(np.diff(seg) >= 0) and seg[-1] == orp[-1] == p["nrec"]
+        q = p["rec_off"].astype(np.int64) // (4 * p["BV"])
+        assert np.all(p["rec_off"] % (4 * p["BV"]) == 0)
         s = q % p["PITCH"]
-        r = (q // p["PITCH"]) % p["NSLOT"]
-        cl = q // (p["PITCH"] * p["NSLOT"])
+        r = (q // p["PITCH"]) % p["IN_ROWS"]
+        cl = q // (p["PITCH"] * p["IN_ROWS"])
+        seen = 0
         for g in range(NG):
-            for ci in range(NCH):
-                for kk in range(KG):
-                    b = (g * NCH + ci) * KG + kk
-                    k = g * KG + kk
-                    lo, hi = seg[b], seg[b + 1]
-                    if k >= K:
-                        assert lo == hi
-                        continue
-                    row = slice(orp[k], orp[k + 1])
-                    flat = oix[row].astype(np.int64)
-                    sel = (flat // (R * S)) // CC == ci        # entries of this chunk, in row order
-                    want_flat = flat[sel]
-                    got_flat = ((cl[lo:hi] + ci * CC) * R + r[lo:hi]) * S + s[lo:hi]
-                    assert np.array_equal(got_flat, want_flat)
-                    assert np.all(cl[lo:hi] < CC) and np.all(r[lo:hi] < R) and np.all(s[lo:hi] < S)
-                    assert np.array_equal(bits(p["rec_val"][lo:hi]), bits(ovl[row][sel]))
+            for wv in range(WV):
+                for ci in range(NCH):
+                    for j in range(SL):
+                        b = ((g * WV + wv) * NCH + ci) * SL + j
+                        k = g * KG + wv * SL + j
+                        lo, hi = seg[b], seg[b + 1]
+                        if k >= K:
+                            assert lo == hi
+                            continue
+                        row = slice(orp[k], orp[k + 1])
+                        flat = oix[row].astype(np.int64)
+                        sel = (flat // (R * S)) // CC == ci        # entries of this chunk, in row order
+                        got_flat = ((cl[lo:hi] + ci * CC) * R + r[lo:hi]) * S + s[lo:hi]
+                        assert np.array_equal(got_flat, flat[sel])
+                        assert np.all(cl[lo:hi] < CC) and np.all(r[lo:hi] < R) and np.all(s[lo:hi] < S)
+                        assert np.array_equal(bits(p["rec_val"][lo:hi]), bits(ovl[row][sel]))
+                        seen += hi - lo
+        assert seen == orp[-1]
 
 
 # ------------------------------------------------------------------ A4-A6: tiled convolution
@@ -184,6 +187,58 @@ def test_dense_filter_equals_dense_convolution(F):
     f = F.filter_compress(dev(w))
     assert f.nnz == w.size
     assert_parity(gpu_conv(F, x, w, (1, 1), (1, 1), b, False, filt=f), o, a, row_nmax(w), "dense")
+
+
+# ------------------------------------------------------------------ batch-interleaved (N4) tensors
+def to_n4(x):
+    """numpy NCHW -> the N4 array ceil(N/4) x C x H x W x 4 (pad images = 0)."""
+    n, c, h, w_ = x.shape
+    g = (n + 3) // 4
+    xp = np.zeros((g * 4, c, h, w_), np.float32)
+    xp[:n] = x
+    return np.ascontiguousarray(xp.reshape(g, 4, c, h, w_).transpose(0, 2, 3, 4, 1))
+
+
+def from_n4(x4, n):
+    g, c, h, w_, _ = x4.shape
+    return np.ascontiguousarray(x4.transpose(0, 4, 1, 2, 3).reshape(g * 4, c, h, w_)[:n])
+
+
+@pytest.mark.parametrize("n", [1, 4, 6])
+def test_layout_convert_and_pool_n4(F, n):
+    x = np.random.default_rng(n).standard_normal((n, 5, 7, 10)).astype(np.float32)
+    x4 = host(F.layout_convert(dev(x), F.NCHW))
+    assert np.array_equal(x4, to_n4(x))
+    assert np.array_equal(host(F.layout_convert(dev(to_n4(x)), F.N4, n=n)), x)
+    p4 = host(F.maxpool2x2(dev(to_n4(x)), layout=F.N4, n=n))
+    assert np.array_equal(from_n4(p4, n), oracle.maxpool2x2(x))
+
+
+@pytest.mark.parametrize("case", [(6, 19, 37, 23, 71, 0.30, (1, 1)), (4, 40, 9, 14, 14, 0.20, (1, 1)),
+                                  (5, 8, 70, 28, 28, 0.10, (1, 1)), (9, 3, 8, 12, 66, 1.0, (0, 0))])
+def test_conv_n4_layouts_match_oracle(F, case):
+    n, c, k, h, w_, keep, pad = case
+    x, w, b = inputs.random_layer(sum(case[:5]), n, c, k, h, w_, 3, 3, keep)
+    o, a = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, (1, 1), pad, b, True, want_abs=True)
+    f = F.filter_compress(dev(w))
+    xs = {F.NCHW: dev(x), F.N4: dev(to_n4(x))}
+    tested = 0
+    for v in [0] + tiled_variants(F):
+        for xl in (F.NCHW, F.N4):
+            for yl in (F.NCHW, F.N4):
+                if xl == F.NCHW and yl == F.NCHW:
+                    continue
+                try:
+                    y = F.conv2d_sparse_filter(f, xs[xl], (1, 1), pad, dev(b), True, variant=v,
+                                               x_layout=xl, y_layout=yl, n=n)
+                except F.FscnnError as e:
+                    assert e.status == 4 and v != 0          # a one-image-per-lane configuration
+                    continue
+                torch.cuda.synchronize()
+                g = host(y) if yl == F.NCHW else from_n4(host(y), n)
+                assert_parity(g, o, a, row_nmax(w), "N4 case %r variant %d layouts %d->%d" % (case, v, xl, yl))
+                tested += 1
+    assert tested >= 6
 
 
 # ------------------------------------------------------------------ direct kernel (any stride / extent)
