@@ -48,7 +48,7 @@ def build_stack(fscnn, torch, inputs, n, keep):
     return torch.from_numpy(x).cuda(), dev_layers, compress_ms
 
 
-def alloc_buffers(fscnn, torch, dev_layers, n):
+def alloc_buffers(fscnn, torch, dev_layers, n, fuse_pool):
     """Output tensors of every layer (and pool), allocated once: the timed loop allocates nothing."""
     last = len(dev_layers) - 1
     for li, d in enumerate(dev_layers):
@@ -58,8 +58,11 @@ def alloc_buffers(fscnn, torch, dev_layers, n):
         d["y"] = torch.empty(shape, dtype=torch.float32, device="cuda")
         d["lay_in"] = fscnn.NCHW if li == 0 else fscnn.N4
         d["lay_out"] = lay_out
-        if d["pool"]:
+        if d["pool"] and fuse_pool:            # the conv launch stores the pooled tensor only
+            d["y"] = torch.empty(fscnn.n4_shape(n, d["k"], hw // 2, hw // 2), dtype=torch.float32, device="cuda")
+        elif d["pool"]:
             d["p"] = torch.empty(fscnn.n4_shape(n, d["k"], hw // 2, hw // 2), dtype=torch.float32, device="cuda")
+        d["fused"] = bool(d["pool"] and fuse_pool)
 
 
 def run_step(fscnn, x, dev_layers, n, events=None):
@@ -68,14 +71,80 @@ def run_step(fscnn, x, dev_layers, n, events=None):
         if events is not None:
             events[li][0].record()
         fscnn.conv2d_sparse_filter(d["f"], cur, (1, 1), (1, 1), d["bias"], d["relu"], out=d["y"],
-                                   x_layout=d["lay_in"], y_layout=d["lay_out"], n=n)
+                                   x_layout=d["lay_in"], y_layout=d["lay_out"], n=n, pool=d["fused"])
         if events is not None:
             events[li][1].record()
         cur = d["y"]
-        if d["pool"]:
+        if d["pool"] and not d["fused"]:
             fscnn.maxpool2x2(cur, out=d["p"], layout=fscnn.N4, n=n)
             cur = d["p"]
     return cur
+
+
+def time_gpu(torch, fn, iters):
+    """Average milliseconds of fn() over `iters` calls (HIP events on the current stream)."""
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def other_rows(fscnn, torch, inputs, np, dev_layers):
+    """The steps of the path that are not inside the timed stack: filter compression and plan
+    build (once per model), activation compression and the sparse-input convolution (workload:
+    the conv4-shaped layer of the sparsity sweep, N=8, C=K=512, 28x28), and the sparse-filter
+    kernel on that layer at the sweep's densities."""
+    out = {}
+    # A1-A3: compress + plan of all 13 layers (includes the two host synchronisations per layer)
+    wbytes = sum(d["w"].numel() * 4 for d in dev_layers)
+
+    def compress_all():
+        for d in dev_layers:
+            f = fscnn.filter_compress(d["w"])
+            fscnn.filter_prepare(f, 32, d["hw"], d["hw"], (1, 1), (1, 1))
+    t0 = time.perf_counter()
+    compress_all()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3
+    out["filter_compress_and_plan"] = dict(ms=ms, dense_weight_bytes=wbytes, gbs=wbytes / ms / 1e6,
+                                           note="13 layers, wall clock incl. allocations and host syncs")
+    # config 5 layer
+    sweep = []
+    for keep in inputs.CONFIG5_KEEP:
+        c = inputs.config5(keep)
+        x = torch.from_numpy(c["x"]).cuda()
+        w = torch.from_numpy(c["w"]).cuda()
+        b = torch.from_numpy(c["bias"]).cuda()
+        f = fscnn.filter_compress(w)
+        y = fscnn.conv2d_sparse_filter(f, x, (1, 1), (1, 1), b, True)
+        ms = time_gpu(torch, lambda: fscnn.conv2d_sparse_filter(f, x, (1, 1), (1, 1), b, True, out=y), 10)
+        feff = 2.0 * f.nnz * 28 * 28 * 8
+        sweep.append(dict(keep=keep, nnz=f.nnz, ms=ms, effective_tflops=feff / ms / 1e9))
+        if keep == 0.05:
+            n, ch, h, wd = c["x"].shape
+            ms_c = time_gpu(torch, lambda: fscnn.input_compress(x), 5)
+            xs = fscnn.input_compress(x)
+            out["input_compress"] = dict(ms=ms_c, nnz=xs.nnz, density=xs.nnz / x.numel(),
+                                         gbs=(x.numel() * 4 + xs.nnz * 8) / ms_c / 1e6,
+                                         note="N=8, C=512, 28x28, ReLU(N(-0.5,1)); incl. allocation and one host sync")
+            y2 = fscnn.conv2d_sparse_input(xs, w, (1, 1), (1, 1), b, True)
+            ms_s = time_gpu(torch, lambda: fscnn.conv2d_sparse_input(xs, w, (1, 1), (1, 1), b, True, out=y2), 5)
+            # effective work: (nonzero input, in-image tap, k) triples
+            nzpix = (c["x"] != 0).sum(axis=1).astype(np.float64)             # N x H x W
+            ty = np.full(h, 3.0); ty[0] = ty[-1] = 2.0
+            tx = np.full(wd, 3.0); tx[0] = tx[-1] = 2.0
+            triples = float((nzpix * ty[None, :, None] * tx[None, None, :]).sum()) * w.shape[0]
+            out["conv2d_sparse_input"] = dict(ms=ms_s, effective_tflops=2.0 * triples / ms_s / 1e9,
+                                              dense_equivalent_tflops=2.0 * w.numel() * h * wd * n / ms_s / 1e9,
+                                              note="same layer, dense 512x512x3x3 filter bank (values of the 95 % "
+                                                   "sparse weights), compressed input")
+    out["sparse_filter_density_sweep_conv4_n8"] = sweep
+    return out
 
 
 def cpu_baseline(inputs, keep, images):
@@ -103,6 +172,9 @@ def main():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--keep", type=float, default=0.05, help="weight density of layers 2..13")
     ap.add_argument("--cpu-images", type=int, default=16, help="images of the oracle-timed sample (0 = skip)")
+    ap.add_argument("--separate-pool", action="store_true",
+                    help="run the 4 max-pools as separate helper kernels instead of the merged conv+pool epilogue")
+    ap.add_argument("--no-rows", action="store_true", help="skip the measurements outside the timed stack")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="run only a plain copy-like kernel of known size (1 GiB read, 1 GiB written) three "
                          "times; used to scale the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
@@ -130,7 +202,7 @@ def main():
         return
     n = args.batch
     x, dev_layers, compress_ms = build_stack(fscnn, torch, inputs, n, args.keep)
-    alloc_buffers(fscnn, torch, dev_layers, n)
+    alloc_buffers(fscnn, torch, dev_layers, n, not args.separate_pool)
 
     # per-layer effective work and algorithmic bytes (x read once, y written once, compressed filter
     # and bias read once)
@@ -197,6 +269,8 @@ def main():
         filter_compress_ms_all_layers=compress_ms,
         roofline=roofline,
     )
+    if not args.no_rows:
+        out["other_rows"] = other_rows(fscnn, torch, inputs, np, dev_layers)
     if args.cpu_images > 0:
         out["cpu_baseline"] = cpu_baseline(inputs, args.keep, args.cpu_images)
     print(json.dumps(out))

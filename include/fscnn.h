@@ -149,6 +149,21 @@ fscnn_status_t fscnn_conv2d_sparse_filter_ex(fscnn_filter_t *f, const float *x_d
                                              int relu, float *y_dev, fscnn_layout_t x_layout,
                                              fscnn_layout_t y_layout, int variant, void *stream);
 
+/* Merged convolution + 2x2 / stride-2 max-pooling (Alg. 7: the convolution's elements update
+ * a running maximum per pooling region and only the pooled values are stored; pooled extent
+ * floor(Ho/2) x floor(Wo/2) as in its step 4).  Same arguments as
+ * fscnn_conv2d_sparse_filter_ex, but y_dev is N x K x floor(Ho/2) x floor(Wo/2) in y_layout
+ * and equals max-pooling applied to that call's output (bias and ReLU before the maximum).
+ * FSCNN_ERR_SHAPE if Ho or Wo < 2; FSCNN_ERR_UNSUPPORTED where only the direct kernel applies
+ * (strides other than 1, filters other than 3x3) or the configuration has no pooled form. */
+fscnn_status_t fscnn_conv2d_sparse_filter_pool2x2(fscnn_filter_t *f, const float *x_dev, int N,
+                                                  int C, int H, int W, int stride_h,
+                                                  int stride_w, int pad_h, int pad_w,
+                                                  const float *bias_dev, int relu, float *y_dev,
+                                                  fscnn_layout_t x_layout,
+                                                  fscnn_layout_t y_layout, int variant,
+                                                  void *stream);
+
 /* Layout conversion of an N x C x H x W tensor (src_layout != dst_layout, no aliasing).
  * Asynchronous on `stream`. */
 fscnn_status_t fscnn_layout_convert(const float *src_dev, int N, int C, int H, int W,

@@ -120,7 +120,7 @@ fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan *
 // Which variant serves this geometry: `variant` > 0 is taken as is (checked), 0 = automatic,
 // anything the tiled kernel cannot do goes to the direct kernel (-1).
 fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int sh, int sw,
-                               int variant, int *resolved)
+                               int variant, int *resolved, bool n4 = false)
 {
     // the tiled kernel addresses up to four images' channels with 32-bit byte offsets
     const bool tiled_ok = (sh == 1 && sw == 1) && (long long)f->C * H * W * 16 < 0x7ffffff0LL;
@@ -131,7 +131,8 @@ fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int
         *resolved = variant;
         return FSCNN_OK;
     }
-    int v = tiled_ok ? sf_choose_variant(N, f->C, f->K, H, W, f->R, f->S) : 0;
+    // N4 tensors need four images per lane whatever the batch size
+    int v = tiled_ok ? sf_choose_variant(n4 && N < 4 ? 4 : N, f->C, f->K, H, W, f->R, f->S) : 0;
     *resolved = v > 0 ? v : -1;
     return FSCNN_OK;
 }
@@ -337,11 +338,10 @@ fscnn_status_t fscnn_filter_destroy(fscnn_filter_t *f)
 int fscnn_sf_variant_count(void) { return sf_variant_count(); }
 const char *fscnn_sf_variant_name(int variant) { return sf_variant_name(variant); }
 
-fscnn_status_t fscnn_conv2d_sparse_filter_ex(fscnn_filter_t *f, const float *x_dev, int N, int C,
-                                             int H, int W, int sh, int sw, int ph, int pw,
-                                             const float *bias_dev, int relu, float *y_dev,
-                                             fscnn_layout_t x_layout, fscnn_layout_t y_layout,
-                                             int variant, void *stream)
+static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int N, int C, int H,
+                                     int W, int sh, int sw, int ph, int pw, const float *bias_dev,
+                                     int relu, float *y_dev, fscnn_layout_t x_layout,
+                                     fscnn_layout_t y_layout, int variant, int pool, void *stream)
 {
     int Ho, Wo;
     fscnn_status_t s = check_conv_args(f, x_dev, N, C, H, W, sh, sw, ph, pw, y_dev, &Ho, &Wo);
@@ -354,10 +354,12 @@ fscnn_status_t fscnn_conv2d_sparse_filter_ex(fscnn_filter_t *f, const float *x_d
     const long long n4 = ((long long)N + 3) / 4 * 4;
     if ((in4 && !fits_int(n4 * C * H * W)) || (out4 && !fits_int(n4 * f->K * Ho * Wo)))
         return FSCNN_ERR_UNSUPPORTED;
+    if (pool && (Ho < 2 || Wo < 2)) return FSCNN_ERR_SHAPE;   // empty pooled output
     int v;
-    s = resolve_variant(f, N, H, W, sh, sw, variant, &v);
+    s = resolve_variant(f, N, H, W, sh, sw, variant, &v, in4 || out4);
     if (s != FSCNN_OK) return s;
-    if ((in4 || out4) && (v < 0 || !sf_variant_has_layout(v, in4, out4))) return FSCNN_ERR_UNSUPPORTED;
+    if ((in4 || out4 || pool) && v < 0) return FSCNN_ERR_UNSUPPORTED;   // the direct kernel: NCHW, no pool
+    if (v > 0 && !sf_variant_has_layout(v, in4, out4, pool)) return FSCNN_ERR_UNSUPPORTED;
     int dev;
     s = have_device(&dev);
     if (s != FSCNN_OK) return s;
@@ -370,9 +372,30 @@ fscnn_status_t fscnn_conv2d_sparse_filter_ex(fscnn_filter_t *f, const float *x_d
                                         f->S, Ho, Wo, sh, sw, ph, pw, bias_dev, relu, y_dev, st));
     } else {
         FSCNN_HIP(launch_conv_sf_tiled(*p, x_dev, N, C, H, W, f->K, Ho, Wo, ph, pw, bias_dev, relu,
-                                       y_dev, in4, out4, st));
+                                       y_dev, in4, out4, pool, st));
     }
     return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_conv2d_sparse_filter_ex(fscnn_filter_t *f, const float *x_dev, int N, int C,
+                                             int H, int W, int sh, int sw, int ph, int pw,
+                                             const float *bias_dev, int relu, float *y_dev,
+                                             fscnn_layout_t x_layout, fscnn_layout_t y_layout,
+                                             int variant, void *stream)
+{
+    return conv_sf_common(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, relu, y_dev, x_layout,
+                          y_layout, variant, 0, stream);
+}
+
+fscnn_status_t fscnn_conv2d_sparse_filter_pool2x2(fscnn_filter_t *f, const float *x_dev, int N,
+                                                  int C, int H, int W, int sh, int sw, int ph,
+                                                  int pw, const float *bias_dev, int relu,
+                                                  float *y_dev, fscnn_layout_t x_layout,
+                                                  fscnn_layout_t y_layout, int variant,
+                                                  void *stream)
+{
+    return conv_sf_common(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, relu, y_dev, x_layout,
+                          y_layout, variant, 1, stream);
 }
 
 fscnn_status_t fscnn_conv2d_sparse_filter_v(fscnn_filter_t *f, const float *x_dev, int N, int C,

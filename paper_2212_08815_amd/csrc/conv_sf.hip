@@ -22,9 +22,9 @@
 //     barrier per chunk separates them;
 //   * per wave the plan holds ONE contiguous stream of records {LDS byte offset of tap
 //     (c mod CC, r, s), weight}, ordered by (chunk, channel slot).  The stream is
-//     wave-uniform: it comes through scalar loads into a small SGPR queue kept 2U-1 records
-//     ahead, and the hot loop handles U records per trip: U address adds, U*NV LDS reads,
-//     U*P fused multiply-adds.
+//     wave-uniform: it comes through scalar loads into a queue of U records in SGPRs, refilled
+//     one trip ahead, and the hot loop handles U records per trip: U address adds, U*NV LDS
+//     reads, U*P fused multiply-adds.
 #include <type_traits>
 
 #include "internal.h"
@@ -34,13 +34,17 @@ namespace fscnn {
 namespace {
 
 template <int BV_, int LW_, int LHR_, int NV_, int SLOTS_, int WAVES_, int CC_, int U_, int NB_, int R_, int S_,
-          bool IN4_ = false, bool OUT4_ = false>
+          bool IN4_ = false, bool OUT4_ = false, bool POOL_ = false>
 struct Cfg {
     static constexpr int BV = BV_, LW = LW_, LHR = LHR_, NV = NV_, SLOTS = SLOTS_, WAVES = WAVES_;
     static constexpr int CC = CC_, U = U_, NB = NB_, R = R_, S = S_;
     // IN4 / OUT4: the input / output tensor is stored batch-interleaved by four ("N4":
     // [N/4][C][H][W][4]) instead of NCHW; then a lane's four images are 16 contiguous bytes
     static constexpr bool IN4 = IN4_, OUT4 = OUT4_;
+    // POOL: the epilogue also applies the 2x2 / stride-2 max-pool (merged convolution and
+    // pooling, Alg. 7) and stores the pooled tensor only
+    static constexpr bool POOL = POOL_;
+    static_assert(!POOL || (NV_ % 2 == 0 && LW_ % 2 == 0), "pooling pairs rows inside a lane and columns of lane pairs");
     static_assert((!IN4 && !OUT4) || BV == 4, "N4 tensors need four images per lane");
     static constexpr int IG = 64 / (LW * LHR);   // image groups across the lanes of a wave
     static_assert(IG * LW * LHR == 64, "lanes must factor as LW * LHR * IG");
@@ -64,7 +68,7 @@ struct Cfg {
     static constexpr int NT = WAVES * 64;
     static constexpr int NIW = (NI + WAVES - 1) / WAVES;   // lines per wave and image group
     static constexpr int ROWSTEP = PITCH * BV * 4;         // bytes from one tile row to the next
-    static constexpr int FIFO = 2 * U - 1;                 // records held ahead in SGPRs
+    static constexpr int FIFO = U;                         // records held ahead in SGPRs
     // loads a wave may leave in flight once the NEXT chunk has to be complete: every wave
     // issues at least IG*(NI/WAVES) lines per chunk, and D-1 younger chunks follow it
     static constexpr int WAITN = (D - 1) * IG * (NI / WAVES) > 63 ? 63 : (D - 1) * IG * (NI / WAVES);
@@ -78,7 +82,7 @@ template <int N> __device__ inline void wait_vmcnt()
 }
 
 constexpr int kInvalidOff = 0x7ffffff0;  // beyond any num_records: the buffer load returns 0
-static_assert(kPlanSpare >= 2 * 4 - 1 + 4, "queue depth plus one step must stay inside the spare records");
+static_assert(kPlanSpare >= 2 * 4, "a queue refill past the last record must stay inside the spare records");
 
 template <int BV> struct VecT;
 template <> struct VecT<1> { using T = float; };
@@ -92,6 +96,12 @@ template <> __device__ inline float vget<4>(const float4 &v, int e)
 {
     return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
 }
+
+// Keeps a loaded value live at this point of the program: the optimiser would otherwise sink
+// an LDS read into the conditional block that consumes it and serialise the reads of a trip.
+__device__ inline void pin(const float &v) { asm volatile("" : : "v"(v)); }
+__device__ inline void pin(const float2 &v) { asm volatile("" : : "v"(v.x), "v"(v.y)); }
+__device__ inline void pin(const float4 &v) { asm volatile("" : : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
 
 typedef int int4v __attribute__((ext_vector_type(4)));
 
@@ -240,39 +250,49 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
 #pragma unroll
         for (int j = 0; j < G::SLOTS; ++j) {
             const int end = bnd[j];
-            // M records per step: read their taps, multiply-add, then advance the queue by M
-            auto step = [&](auto mtag) {
-                constexpr int M = decltype(mtag)::value;
-                V in[M][G::NV];
+            // U records per trip.  The queue q[0..U-1] always holds the U records that start at
+            // stream position i; a trip reads the taps of all U, refills the queue from where the
+            // next trip starts (i + U, or the segment end if that comes first: the stream is
+            // contiguous, so that is where the next slot's records begin), and multiply-adds only
+            // the records that belong to this slot.
+            while (i < end) {
+                const int left = end - i;
+                const int ni = left < G::U ? end : i + G::U;
+                V in[G::U][G::NV];
 #pragma unroll
-                for (int m = 0; m < M; ++m) {
+                for (int m = 0; m < G::U; ++m) {
                     const char *p = tile + q[m].off;
 #pragma unroll
                     for (int v = 0; v < G::NV; ++v)
                         in[m][v] = *reinterpret_cast<const V *>(p + v * G::ROWSTEP);
                 }
-                Rec fresh[M];
+                Rec fresh[G::U];
 #pragma unroll
-                for (int m = 0; m < M; ++m) fresh[m] = recs[i + G::FIFO + m];
+                for (int m = 0; m < G::U; ++m) fresh[m] = recs[ni + m];
+                if constexpr (G::U > 1) {
 #pragma unroll
-                for (int m = 0; m < M; ++m)
+                    for (int m = 1; m < G::U; ++m)
 #pragma unroll
-                    for (int v = 0; v < G::NV; ++v)
+                        for (int v = 0; v < G::NV; ++v) pin(in[m][v]);
+                    // likewise the refill: issue it with the reads, not after the multiply-adds
 #pragma unroll
-                        for (int b = 0; b < G::BV; ++b)
-                            acc[j][v * G::BV + b] = __builtin_fmaf(
-                                q[m].val, vget<G::BV>(in[m][v], b), acc[j][v * G::BV + b]);
+                    for (int m = 0; m < G::U; ++m) asm volatile("" : : "s"(fresh[m].off), "s"(fresh[m].val));
+                }
 #pragma unroll
-                for (int f = 0; f + M < G::FIFO; ++f) q[f] = q[f + M];
+                for (int m = 0; m < G::U; ++m) {
+                    if (m == 0 || m < left) {
 #pragma unroll
-                for (int m = 0; m < M; ++m) q[G::FIFO - M + m] = fresh[m];
-                i += M;
-            };
-            while (end - i >= G::U) step(std::integral_constant<int, G::U>());
-            if constexpr (G::U >= 4)
-                if (end - i >= 2) step(std::integral_constant<int, 2>());
-            if constexpr (G::U >= 2)
-                if (end - i >= 1) step(std::integral_constant<int, 1>());
+                        for (int v = 0; v < G::NV; ++v)
+#pragma unroll
+                            for (int b = 0; b < G::BV; ++b)
+                                acc[j][v * G::BV + b] = __builtin_fmaf(
+                                    q[m].val, vget<G::BV>(in[m][v], b), acc[j][v * G::BV + b]);
+                    }
+                }
+#pragma unroll
+                for (int m = 0; m < G::U; ++m) q[m] = fresh[m];
+                i = ni;
+            }
             i = end;  // boundaries never decrease, so the steps above always end exactly here
         }
 #pragma unroll
@@ -284,6 +304,49 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
 
     // ---- epilogue (A6): bias, ReLU, store (coalesced along x)
     const int ox = tx0 + lx;
+    if constexpr (G::POOL) {
+        // merged 2x2 max-pool: rows pair up inside a lane (tile rows start even), columns across
+        // the lane pair (lx, lx^1); adding the bias and the ReLU commute with the maximum
+        const int Hp = Ho / 2, Wp = Wo / 2;
+        const long long pplane = (long long)Hp * Wp;
+        const int px = ox >> 1;
+#pragma unroll
+        for (int j = 0; j < G::SLOTS; ++j) {
+            const int k = kg * G::KG + wave * G::SLOTS + j;
+            if (k >= K) break;
+            const float bk = bias ? bias[k] : 0.0f;
+#pragma unroll
+            for (int v = 0; v < G::NV; v += 2) {
+                const int py = (ty0 + lh * G::NV + v) >> 1;
+                float r[G::BV];
+#pragma unroll
+                for (int b = 0; b < G::BV; ++b) {
+                    const float a0 = acc[j][v * G::BV + b], a1 = acc[j][(v + 1) * G::BV + b];
+                    float m = a1 > a0 ? a1 : a0;
+                    const float o = __shfl_xor(m, 1, 64);
+                    m = o > m ? o : m;
+                    m += bk;
+                    if (relu) m = m > 0.0f ? m : 0.0f;
+                    r[b] = m;
+                }
+                const bool ok = (lx & 1) == 0 && py < Hp && px < Wp;
+                if constexpr (G::OUT4) {
+                    const int n = n0 + ig * 4;
+                    if (ok && n < N)
+                        reinterpret_cast<float4 *>(y)[((long long)(n / 4) * K + k) * pplane +
+                                                      (long long)py * Wp + px] =
+                            make_float4(r[0], r[1], r[2], r[3]);
+                } else {
+#pragma unroll
+                    for (int b = 0; b < G::BV; ++b) {
+                        const int n = n0 + ig * G::BV + b;
+                        if (ok && n < N) y[((long long)n * K + k) * pplane + (long long)py * Wp + px] = r[b];
+                    }
+                }
+            }
+        }
+        return;
+    }
     const long long plane = (long long)Ho * Wo;
 #pragma unroll
     for (int j = 0; j < G::SLOTS; ++j) {
@@ -401,11 +464,15 @@ template <class G> SfGeom geom_of()
 struct Variant {
     const char *name;
     SfGeom g;
-    LaunchFn fn[2][2];  // [input is N4][output is N4]; null where the configuration has no such form
+    LaunchFn fn[2][2];    // [input is N4][output is N4]; null where the configuration has no such form
+    LaunchFn pool[2][2];  // same with the merged 2x2 max-pool epilogue
 };
 
 #define FSCNN_CFG(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, I4, O4) \
     Cfg<BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, 3, 3, I4, O4>
+#define FSCNN_CFGP(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, I4, O4) \
+    Cfg<BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, 3, 3, I4, O4, true>
+#define FSCNN_NOPOOL {{nullptr, nullptr}, {nullptr, nullptr}}
 #define FSCNN_NAME(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB) \
     "bv" #BV "_lw" #LW "x" #LHR "_nv" #NV "_s" #SLOTS "_w" #WAVES "_cc" #CC "_u" #U "_nb" #NB
 // four images per lane: all four layout combinations
@@ -415,35 +482,50 @@ struct Variant {
      {{&launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>,       \
        &launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, true)>},       \
       {&launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, false)>,        \
-       &launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, true)>}}}
+       &launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, true)>}},       \
+     FSCNN_NOPOOL}
+// the same plus the pooled forms (the configurations the automatic choice uses)
+#define FSCNN_V4P(LW, LHR, NV, SLOTS, WAVES, CC, U, NB)                                       \
+    {FSCNN_NAME(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB),                                     \
+     geom_of<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>(),             \
+     {{&launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>,       \
+       &launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, true)>},       \
+      {&launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, false)>,        \
+       &launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, true)>}},       \
+     {{&launch_tiled<FSCNN_CFGP(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>,      \
+       &launch_tiled<FSCNN_CFGP(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, true)>},      \
+      {&launch_tiled<FSCNN_CFGP(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, false)>,       \
+       &launch_tiled<FSCNN_CFGP(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, true)>}}}
+// four images per lane, N4 in and out only (tuning candidates)
+#define FSCNN_V4X(LW, LHR, NV, SLOTS, WAVES, CC, U, NB)                                       \
+    {FSCNN_NAME(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB) "_n4only",                           \
+     geom_of<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, true)>(),               \
+     {{nullptr, nullptr},                                                                     \
+      {nullptr, &launch_tiled<FSCNN_CFG(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, true)>}}, \
+     FSCNN_NOPOOL}
 // one or two images per lane: NCHW only
 #define FSCNN_V(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB)                                     \
     {FSCNN_NAME(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB),                                    \
      geom_of<FSCNN_CFG(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>(),            \
      {{&launch_tiled<FSCNN_CFG(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>, nullptr}, \
+      {nullptr, nullptr}},                                                                    \
+     {{&launch_tiled<FSCNN_CFGP(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>, nullptr}, \
       {nullptr, nullptr}}}
 
 const Variant *variants(int *count)
 {
     static const Variant table[] = {
-        FSCNN_V4(64, 1, 4, 4, 8, 4, 1, 3),    //  1
-        FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),   //  2
-        FSCNN_V4(64, 1, 4, 8, 8, 8, 1, 3),    //  3
-        FSCNN_V4(64, 1, 4, 4, 8, 8, 1, 2),    //  4
-        FSCNN_V4(32, 1, 4, 4, 8, 4, 1, 3),    //  5
-        FSCNN_V4(32, 1, 4, 4, 16, 8, 1, 3),   //  6
-        FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),    //  7
-        FSCNN_V4(16, 4, 4, 2, 8, 8, 1, 3),    //  8
-        FSCNN_V4(16, 4, 4, 4, 8, 4, 1, 3),    //  9
-        FSCNN_V4(16, 4, 4, 4, 4, 8, 1, 3),    // 10
-        FSCNN_V4(16, 4, 4, 2, 16, 4, 1, 4),   // 11
-        FSCNN_V4(16, 2, 4, 4, 8, 4, 1, 3),    // 12
-        FSCNN_V4(16, 4, 4, 1, 16, 4, 1, 4),   // 13
-        FSCNN_V4(32, 2, 4, 4, 16, 8, 1, 3),   // 14
-        FSCNN_V4(32, 2, 4, 4, 8, 4, 1, 3),    // 15
-        FSCNN_V(1, 64, 1, 8, 8, 8, 8, 1, 2),  // 16
-        FSCNN_V(1, 32, 2, 8, 8, 8, 8, 1, 2),  // 17
-        FSCNN_V(1, 16, 4, 4, 8, 8, 8, 1, 2),  // 18
+        FSCNN_V4P(32, 2, 4, 4, 8, 4, 1, 3),    //  1  wide, few-channel layers (two groups per CU)
+        FSCNN_V4P(32, 2, 4, 4, 16, 14, 1, 2),  //  2  56x56 / 28x28: 16 waves, large chunks
+        FSCNN_V4P(16, 4, 4, 2, 8, 14, 1, 2),   //  3  14x14: whole image per tile, 2 channels per wave
+        FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),    //  4  64-wide rows
+        FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),     //  5  16 images per group
+        FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  //  6  two records per trip
+        FSCNN_V4X(32, 2, 4, 8, 8, 14, 1, 2),   //  7  eight channels per wave
+        FSCNN_V(1, 64, 1, 8, 8, 8, 8, 1, 2),   //  8  one image per lane (N < 4)
+        FSCNN_V(1, 32, 2, 8, 8, 8, 8, 1, 2),   //  9
+        FSCNN_V(1, 16, 4, 4, 8, 8, 8, 1, 2),   // 10
+        FSCNN_V(2, 64, 1, 4, 8, 8, 8, 2, 2),   // 11  two images per lane
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
@@ -476,36 +558,64 @@ bool sf_variant_geom(int variant, int R, int S, SfGeom *g)
     return true;
 }
 
-bool sf_variant_has_layout(int variant, int in4, int out4)
+bool sf_variant_has_layout(int variant, int in4, int out4, int pool)
 {
     int n;
     const Variant *t = variants(&n);
     if (variant < 1 || variant > n) return false;
-    return t[variant - 1].fn[in4 ? 1 : 0][out4 ? 1 : 0] != nullptr;
+    const Variant &v = t[variant - 1];
+    return (pool ? v.pool : v.fn)[in4 ? 1 : 0][out4 ? 1 : 0] != nullptr;
 }
 
-// Automatic choice: lanes-per-row follows the output width so that few lanes idle; batches of
-// at least four images use the image-interleaved (b128) configurations.
+// Work-groups a configuration launches for a layer.
+static long long sf_blocks(const SfGeom &g, int N, int K, int Ho, int Wo)
+{
+    const long long tiles = (long long)((Wo + g.TW - 1) / g.TW) * ((Ho + g.TH - 1) / g.TH);
+    return tiles * ((K + g.KG - 1) / g.KG) * ((N + g.IMGS - 1) / g.IMGS);
+}
+
+// Automatic choice.  Batches of at least four images use the image-interleaved (b128)
+// configurations.  Preference order measured on VGG16-shaped layers (N = 32, 95 % sparse):
+// 32x8 output tiles; 8-wave groups with small chunks for the wide, few-channel layers; 16-wave
+// groups (half the re-staging of the input) with the largest chunks LDS holds twice from 56x56
+// down (fewer barriers, more records per wave between them); whole-image 16x16 tiles with two
+// channels per wave for 14x14.  A configuration that would launch too few work-groups to
+// cover the 256 compute units yields to the next one with smaller groups.
 int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S)
 {
-    (void)C; (void)K; (void)H;
+    (void)C;
     if (R != 3 || S != 3) return 0;
-    // measured on VGG16-shaped layers (N = 32, 95 % sparse): 32x8 output tiles throughout, with
-    // 8-wave groups for the wide, few-channel layers and 16-wave groups (half the re-staging of
-    // the input) from 56x56 down; whole-image 16x16 tiles with two channels per wave (more
-    // work-groups) for 14x14
-    if (N >= 4) return W > 64 ? 15 : W > 16 ? 14 : 8;
-    return W > 32 ? 16 : W > 16 ? 17 : 18;
+    int n;
+    const Variant *t = variants(&n);
+    int pref[3];
+    if (N >= 4) {
+        if (W > 64) { pref[0] = 1; pref[1] = 2; pref[2] = 3; }
+        else if (W > 16) { pref[0] = 2; pref[1] = 1; pref[2] = 3; }
+        else { pref[0] = 3; pref[1] = 3; pref[2] = 3; }
+    } else {
+        if (W > 32) { pref[0] = 8; pref[1] = 9; pref[2] = 10; }
+        else if (W > 16) { pref[0] = 9; pref[1] = 10; pref[2] = 10; }
+        else { pref[0] = 10; pref[1] = 10; pref[2] = 10; }
+    }
+    int best = pref[0];
+    long long best_blocks = -1;
+    for (int i = 0; i < 3; ++i) {
+        const long long b = sf_blocks(t[pref[i] - 1].g, N, K, H, W);  // Ho, Wo ~ H, W for this purpose
+        if (b >= 192) return pref[i];
+        if (b > best_blocks) { best_blocks = b; best = pref[i]; }
+    }
+    return best;
 }
 
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
-                                float *y, int in4, int out4, hipStream_t st)
+                                float *y, int in4, int out4, int pool, hipStream_t st)
 {
     int n;
     const Variant *t = variants(&n);
     if (p.variant < 1 || p.variant > n) return hipErrorInvalidValue;
-    LaunchFn fn = t[p.variant - 1].fn[in4 ? 1 : 0][out4 ? 1 : 0];
+    const Variant &v = t[p.variant - 1];
+    LaunchFn fn = (pool ? v.pool : v.fn)[in4 ? 1 : 0][out4 ? 1 : 0];
     if (!fn) return hipErrorInvalidValue;
     return fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, st);
 }

@@ -27,7 +27,7 @@ EXPORTS = [
     "fscnn_conv2d_sparse_filter", "fscnn_conv2d_sparse_filter_v", "fscnn_input_compress",
     "fscnn_input_info", "fscnn_input_export", "fscnn_input_destroy", "fscnn_conv2d_sparse_input",
     "fscnn_maxpool2x2", "fscnn_conv2d_sparse_filter_ex", "fscnn_layout_convert",
-    "fscnn_maxpool2x2_ex",
+    "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2",
 ]
 
 NCHW, N4 = 0, 1      # fscnn_layout_t
@@ -202,14 +202,17 @@ def _logical_shape(x, layout, n):
 
 
 def conv2d_sparse_filter(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=False, out=None, variant=0,
-                         x_layout=NCHW, y_layout=NCHW, n=None):
-    """fscnn_conv2d_sparse_filter_ex: x -> y (CUDA float32).  NCHW tensors are N x C x H x W;
-    N4 tensors are ceil(N/4) x C x H x W x 4 with `n` the number of real images."""
+                         x_layout=NCHW, y_layout=NCHW, n=None, pool=False):
+    """fscnn_conv2d_sparse_filter_ex (or, with pool=True, fscnn_conv2d_sparse_filter_pool2x2):
+    x -> y (CUDA float32).  NCHW tensors are N x C x H x W; N4 tensors are
+    ceil(N/4) x C x H x W x 4 with `n` the number of real images."""
     x = _dev_f32(x, "x")
     bias = _dev_f32(bias, "bias")
     N, C, H, W = _logical_shape(x, x_layout, n)
     K, _, R, S = f.shape
     Ho, Wo = conv2d_out_shape(H, W, R, S, stride, pad)
+    if pool:
+        Ho, Wo = Ho // 2, Wo // 2
     oshape = (N, K, Ho, Wo) if y_layout == NCHW else n4_shape(N, K, Ho, Wo)
     if out is None:
         out = torch.empty(oshape, dtype=torch.float32, device=x.device)
@@ -219,11 +222,11 @@ def conv2d_sparse_filter(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=False,
             raise TypeError("out has the wrong shape")
     if bias is not None and bias.numel() != K:
         raise TypeError("bias must have K entries")
-    _check(lib().fscnn_conv2d_sparse_filter_ex(f.handle, _ptr(x), _i(N), _i(C), _i(H), _i(W),
-                                               _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]),
-                                               _ptr(bias), _i(bool(relu)), _ptr(out), _i(x_layout),
-                                               _i(y_layout), _i(variant), _stream()),
-           "fscnn_conv2d_sparse_filter_ex")
+    fn = lib().fscnn_conv2d_sparse_filter_pool2x2 if pool else lib().fscnn_conv2d_sparse_filter_ex
+    _check(fn(f.handle, _ptr(x), _i(N), _i(C), _i(H), _i(W), _i(stride[0]), _i(stride[1]), _i(pad[0]),
+              _i(pad[1]), _ptr(bias), _i(bool(relu)), _ptr(out), _i(x_layout), _i(y_layout), _i(variant),
+              _stream()),
+           "fscnn_conv2d_sparse_filter_pool2x2" if pool else "fscnn_conv2d_sparse_filter_ex")
     return out
 
 

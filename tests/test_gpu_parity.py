@@ -46,8 +46,10 @@ def gpu_conv(F, x, w, stride, pad, bias, relu, variant=0, filt=None):
     return host(y)
 
 
-def tiled_variants(F):
-    return list(range(1, F.sf_variant_count() + 1))
+def tiled_variants(F, n4_only=False):
+    """Kernel configurations that take NCHW tensors (or, with n4_only, those built for N4 only)."""
+    return [v for v in range(1, F.sf_variant_count() + 1)
+            if F.sf_variant_name(v).endswith("_n4only") == n4_only]
 
 
 # ------------------------------------------------------------------ A1/A2: filter compression
@@ -223,7 +225,7 @@ def test_conv_n4_layouts_match_oracle(F, case):
     f = F.filter_compress(dev(w))
     xs = {F.NCHW: dev(x), F.N4: dev(to_n4(x))}
     tested = 0
-    for v in [0] + tiled_variants(F):
+    for v in [0] + tiled_variants(F) + tiled_variants(F, n4_only=True):
         for xl in (F.NCHW, F.N4):
             for yl in (F.NCHW, F.N4):
                 if xl == F.NCHW and yl == F.NCHW:
@@ -238,7 +240,40 @@ def test_conv_n4_layouts_match_oracle(F, case):
                 g = host(y) if yl == F.NCHW else from_n4(host(y), n)
                 assert_parity(g, o, a, row_nmax(w), "N4 case %r variant %d layouts %d->%d" % (case, v, xl, yl))
                 tested += 1
-    assert tested >= 6
+    assert tested >= 6 + len(tiled_variants(F, n4_only=True))
+
+
+# ------------------------------------------------------------------ merged convolution + max-pool
+@pytest.mark.parametrize("case", [(6, 19, 37, 23, 71, 0.30, (1, 1)), (4, 40, 9, 14, 14, 0.20, (1, 1)),
+                                  (1, 8, 70, 28, 28, 0.10, (1, 1)), (5, 3, 8, 13, 66, 1.0, (0, 0))])
+def test_merged_conv_pool_matches_oracle_conv_then_pool(F, case):
+    n, c, k, h, w_, keep, pad = case
+    x, w, b = inputs.random_layer(sum(case[:5]) + 1, n, c, k, h, w_, 3, 3, keep)
+    oc, a = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, (1, 1), pad, b, True, want_abs=True)
+    o = oracle.maxpool2x2(oc)
+    amax = oracle.maxpool2x2(a.astype(np.float32)).astype(np.float64) * (1 + 1e-6)   # bound of the window's worst element
+    f = F.filter_compress(dev(w))
+    xs = {F.NCHW: dev(x), F.N4: dev(to_n4(x))}
+    tested = 0
+    for v in [0] + tiled_variants(F):
+        for xl in (F.NCHW, F.N4):
+            for yl in (F.NCHW, F.N4):
+                try:
+                    y = F.conv2d_sparse_filter(f, xs[xl], (1, 1), pad, dev(b), True, variant=v, x_layout=xl,
+                                               y_layout=yl, n=n, pool=True)
+                except F.FscnnError as e:
+                    assert e.status == 4 and v != 0
+                    continue
+                torch.cuda.synchronize()
+                g = host(y) if yl == F.NCHW else from_n4(host(y), n)
+                assert_parity(g, o, amax, row_nmax(w), "pool case %r variant %d layouts %d->%d" % (case, v, xl, yl))
+                tested += 1
+    assert tested >= 4
+    # integer data: bit-exact against conv-then-pool
+    xi, wi, bi = inputs.random_layer(7, n, c, k, h, w_, 3, 3, keep, integer=True)
+    want = oracle.maxpool2x2(oracle.conv2d_dense(xi, wi, (1, 1), pad, bi, True))
+    got = host(F.conv2d_sparse_filter(F.filter_compress(dev(wi)), dev(xi), (1, 1), pad, dev(bi), True, pool=True))
+    assert np.array_equal(got, want)
 
 
 # ------------------------------------------------------------------ direct kernel (any stride / extent)
