@@ -53,13 +53,34 @@ struct Cfg {
     static constexpr int P = NV * BV;            // accumulators per lane and channel
     static constexpr int TH = LHR * NV, TW = LW; // output tile
     static constexpr int IN_ROWS = TH + R - 1;
-    static constexpr int PITCH = TW + S - 1;
+    // LDS serves a wide read of lane i together with lane i+32 (measured: the 16x4 lane shape
+    // showed a 50 % bank-conflict rate, the 32x2 shape none), so the byte offset of lane 32's
+    // vector must be 128 modulo 256; where lane 32 starts another row group the row pitch is
+    // padded until that holds.  (With 64 lanes in one row, or lane 32 in another image group,
+    // the offset is fixed by the layout.)
+    static constexpr int pick_pitch()
+    {
+        int p = TW + S - 1;
+        if (LW < 64 && LHR > 1 && BV * 4 == 16)
+            while ((((32 / LW) * NV * p * 16) % 256) != 128 && p < TW + S - 1 + 16) ++p;
+        return p;
+    }
+    static constexpr int PITCH = pick_pitch();
     static constexpr int IG_ELEMS = CC * IN_ROWS * PITCH;  // BV-vectors per image group
     static constexpr int IG_DW = IG_ELEMS * BV;            // dwords per image group
     // one staging load fills an LDS line of 64 dwords (NCHW input) or 64 BV-vectors (N4 input)
     static constexpr int LINE_BYTES = IN4 ? 1024 : 256;
     static constexpr int NI = IN4 ? (IG_ELEMS + 63) / 64 : (IG_DW + 63) / 64;  // lines per image group
-    static constexpr int IG_BYTES = NI * LINE_BYTES;       // padded so that a line never spills
+    // padded so that a line never spills; where lane 32 belongs to another image group the
+    // group stride is nudged so that lane 32 sits 128 bytes (mod 256) from lane 0 (see PITCH)
+    static constexpr int pick_ig_bytes()
+    {
+        int b = NI * LINE_BYTES;
+        if (LW * LHR <= 32 && BV * 4 == 16)
+            while ((((32 / (LW * LHR)) * b) % 256) != 128) b += 16;
+        return b;
+    }
+    static constexpr int IG_BYTES = pick_ig_bytes();
     static constexpr int BUF_BYTES = IG * IG_BYTES;
     static constexpr int LDS_BYTES = NB * BUF_BYTES;
     static constexpr int D = NB - 1;                       // chunks whose loads run ahead
@@ -179,7 +200,10 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
         goff[q] = !ok ? kInvalidOff : G::IN4 ? pix * 16 : (b * C * HW + pix) * 4;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ldsb;
-    auto fetch = [&](int ci, int buf) {
+    // Lines q with q % nparts == part only: the loads of a chunk are issued in SLOTS portions
+    // spread over the computation of the previous chunk, so that the waves do not all queue at
+    // the memory pipeline right after a barrier while the vector ALUs idle.
+    auto fetch = [&](int ci, int buf, int part, int nparts) {
         const int crem = C - ci * G::CC;  // channels left from this chunk on (> 0)
 #pragma unroll
         for (int g = 0; g < G::IG; ++g) {
@@ -199,7 +223,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                 const int line = wave + q * G::WAVES;
                 const uint32_t dst =
                     lds0 + (uint32_t)(buf * G::BUF_BYTES + g * G::IG_BYTES + line * G::LINE_BYTES);
-                if (line < G::NI) {
+                if (line < G::NI && q % nparts == part) {
                     if constexpr (G::IN4) lds_dma_dwordx4(rs, dst, goff[q]);
                     else lds_dma_dword(rs, dst, goff[q]);
                 }
@@ -226,7 +250,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     // the first D chunks start loading; chunk 0 must have landed before anyone reads it
 #pragma unroll
     for (int d = 0; d < G::D; ++d)
-        if (d < NCH) fetch(d, d);
+        if (d < NCH) fetch(d, d, 0, 1);
     if (G::D <= NCH) wait_vmcnt<G::WAITN>(); else wait_vmcnt<0>();
     __syncthreads();
 
@@ -234,8 +258,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     int wbuf = G::D;      // ring slot the next load goes to (last read one chunk ago)
     for (int ci = 0; ci < NCH; ++ci) {
         int nbnd[G::SLOTS];
-        if (ci + G::D < NCH) fetch(ci + G::D, wbuf);  // in flight while D chunks are computed
-        wbuf = wbuf + 1 == G::NB ? 0 : wbuf + 1;
+        const bool more = ci + G::D < NCH;  // chunk ci+D is loaded while D chunks are computed
         if (ci + 1 < NCH) {
 #pragma unroll
             for (int j = 0; j < G::SLOTS; ++j) nbnd[j] = seg[(ci + 1) * G::SLOTS + j + 1];
@@ -249,6 +272,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
         // ---- gather-FMA over this wave's records of the chunk (A5)
 #pragma unroll
         for (int j = 0; j < G::SLOTS; ++j) {
+            if (more) fetch(ci + G::D, wbuf, j, G::SLOTS);
             const int end = bnd[j];
             // U records per trip.  The queue q[0..U-1] always holds the U records that start at
             // stream position i; a trip reads the taps of all U, refills the queue from where the
@@ -295,6 +319,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
             }
             i = end;  // boundaries never decrease, so the steps above always end exactly here
         }
+        wbuf = wbuf + 1 == G::NB ? 0 : wbuf + 1;
 #pragma unroll
         for (int j = 0; j < G::SLOTS; ++j) bnd[j] = nbnd[j];
         // the next chunk's lines of this wave must be in LDS before the barrier lets anyone read
@@ -521,7 +546,7 @@ const Variant *variants(int *count)
         FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),    //  4  64-wide rows
         FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),     //  5  16 images per group
         FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  //  6  two records per trip
-        FSCNN_V4X(32, 2, 4, 8, 8, 14, 1, 2),   //  7  eight channels per wave
+        FSCNN_V4X(32, 1, 4, 4, 16, 11, 1, 2),  //  7  32x4 tiles of 8 images (rows of 28 divide evenly)
         FSCNN_V(1, 64, 1, 8, 8, 8, 8, 1, 2),   //  8  one image per lane (N < 4)
         FSCNN_V(1, 32, 2, 8, 8, 8, 8, 1, 2),   //  9
         FSCNN_V(1, 16, 4, 4, 8, 8, 8, 1, 2),   // 10
