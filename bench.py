@@ -245,6 +245,10 @@ def main():
                     hbm_frac=balg[dom] / (layer_ms[dom] * 1e-3) / 1e9 / HBM_PEAK_GBS)
     # measured HBM bytes of that launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy
     # kernel of known size): taken from the committed summary of the same workload, else null
+    # what the chip sustains on the hot loop's instruction mix alone (one LDS word per FMA)
+    ceiling = fscnn.probe_gather_fma()
+    roofline["measured_gather_fma_ceiling"] = ceiling
+    roofline["frac_of_measured_ceiling"] = dom_tflops / ceiling
     traffic_file = os.path.join(ROOT, "profiles", "conv_sf_vgg16_n32_hbm_traffic.txt")
     if os.path.exists(traffic_file) and n == 32 and abs(args.keep - 0.05) < 1e-9:
         for line in open(traffic_file):

@@ -203,6 +203,14 @@ fscnn_status_t fscnn_maxpool2x2(const float *x_dev, int N, int C, int H, int W, 
 fscnn_status_t fscnn_maxpool2x2_ex(const float *x_dev, int N, int C, int H, int W, float *y_dev,
                                    fscnn_layout_t layout, void *stream);
 
+/* Measurement helper (no counterpart in the paper): launches `work_groups` groups of 256 threads
+ * that each repeat, `iters` times, the instruction mix of the convolution's hot loop on a
+ * resident LDS tile -- 1 address add, 4 conflict-free ds_read_b128 (16 words per lane), 16 FMAs
+ * with a scalar weight -- with no sparsity, staging or barriers.  The caller times it; the
+ * flop count is work_groups * 256 * iters * 32.  scratch_dev: at least 2 floats, the first one
+ * is read as the weight.  Asynchronous on `stream`. */
+fscnn_status_t fscnn_probe_gather_fma(float *scratch_dev, int iters, int work_groups, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

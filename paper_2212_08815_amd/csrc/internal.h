@@ -108,6 +108,8 @@ hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const f
                                  int Ho, int Wo, int sh, int sw, int ph, int pw, const float *bias,
                                  int relu, float *y, hipStream_t st);
 
+hipError_t run_gather_fma_probe(float *scratch_dev, int iters, int blocks, hipStream_t st);
+
 // ---- conv_si.hip
 constexpr int kSiCC = 16;
 bool si_tiled_supported(int K, int C, int R, int S, int sh, int sw);

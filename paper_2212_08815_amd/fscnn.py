@@ -27,7 +27,7 @@ EXPORTS = [
     "fscnn_conv2d_sparse_filter", "fscnn_conv2d_sparse_filter_v", "fscnn_input_compress",
     "fscnn_input_info", "fscnn_input_export", "fscnn_input_destroy", "fscnn_conv2d_sparse_input",
     "fscnn_maxpool2x2", "fscnn_conv2d_sparse_filter_ex", "fscnn_layout_convert",
-    "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2",
+    "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2", "fscnn_probe_gather_fma",
 ]
 
 NCHW, N4 = 0, 1      # fscnn_layout_t
@@ -321,3 +321,17 @@ def maxpool2x2(x, out=None, layout=NCHW, n=None):
     _check(lib().fscnn_maxpool2x2_ex(_ptr(x), _i(N), _i(C), _i(H), _i(W), _ptr(out), _i(layout),
                                      _stream()), "fscnn_maxpool2x2_ex")
     return out
+
+
+def probe_gather_fma(iters=20000, work_groups=2048):
+    """fscnn_probe_gather_fma timed with HIP events: TFLOP/s the chip sustains on the hot loop's
+    instruction mix (one LDS word per fused multiply-add) without sparsity, staging or barriers."""
+    scratch = torch.ones(4, dtype=torch.float32, device="cuda")
+    _check(lib().fscnn_probe_gather_fma(_ptr(scratch), _i(100), _i(work_groups), _stream()), "fscnn_probe_gather_fma")
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    _check(lib().fscnn_probe_gather_fma(_ptr(scratch), _i(iters), _i(work_groups), _stream()), "fscnn_probe_gather_fma")
+    b.record()
+    torch.cuda.synchronize()
+    return work_groups * 256.0 * iters * 32.0 / (a.elapsed_time(b) * 1e-3) / 1e12
