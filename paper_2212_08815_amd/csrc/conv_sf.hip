@@ -48,6 +48,7 @@ struct Cfg {
     static_assert((!IN4 && !OUT4) || BV == 4, "N4 tensors need four images per lane");
     static constexpr int IG = 64 / (LW * LHR);   // image groups across the lanes of a wave
     static_assert(IG * LW * LHR == 64, "lanes must factor as LW * LHR * IG");
+    // U records per trip of the inner loop: their taps are read together, then multiplied
     static_assert(U == 1 || U == 2 || U == 4, "records per trip");
     static constexpr int IMGS = BV * IG;         // images per work-group
     static constexpr int P = NV * BV;            // accumulators per lane and channel
@@ -93,6 +94,19 @@ struct Cfg {
     // loads a wave may leave in flight once the NEXT chunk has to be complete: every wave
     // issues at least IG*(NI/WAVES) lines per chunk, and D-1 younger chunks follow it
     static constexpr int WAITN = (D - 1) * IG * (NI / WAVES) > 63 ? 63 : (D - 1) * IG * (NI / WAVES);
+    // Waves per SIMD the register allocation aims at: as many work-groups per CU as the LDS
+    // holds, as long as every wave still gets its accumulators, its taps and about two dozen
+    // registers of addressing (512 vector registers per SIMD lane, 4 SIMDs per CU).
+    static constexpr int pick_wpe()
+    {
+        const int need = P * SLOTS + U * P + 24;
+        for (int g = 160 * 1024 / LDS_BYTES; g > 1; --g) {
+            const int w = (g * WAVES + 3) / 4;
+            if (w <= 8 && 512 / w >= need) return w;
+        }
+        return (WAVES + 3) / 4;
+    }
+    static constexpr int WPE = pick_wpe();
 };
 
 // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt is split over
@@ -125,6 +139,7 @@ __device__ inline void pin(const float2 &v) { asm volatile("" : : "v"(v.x), "v"(
 __device__ inline void pin(const float4 &v) { asm volatile("" : : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
 
 typedef int int4v __attribute__((ext_vector_type(4)));
+typedef float f4v __attribute__((ext_vector_type(4)));
 
 // One buffer load that writes LDS directly (MUBUF with LDS=1): lane l deposits the dword it
 // loads at LDS byte address lds_addr + 4*l; a lane whose offset is out of the descriptor's
@@ -157,7 +172,7 @@ __device__ inline int xcd_remap(int bid, int nblk)
 }
 
 template <class G>
-__global__ void __launch_bounds__(G::NT)
+__global__ void __launch_bounds__(G::NT, G::WPE)
 conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                      const float *__restrict__ bias, const Rec *__restrict__ recs,
                      const int *__restrict__ segptr, int N, int C, int H, int W, int K, int Ho,
@@ -540,17 +555,20 @@ struct Variant {
 const Variant *variants(int *count)
 {
     static const Variant table[] = {
-        FSCNN_V4P(32, 2, 4, 4, 8, 4, 1, 3),    //  1  wide, few-channel layers (two groups per CU)
-        FSCNN_V4P(32, 2, 4, 4, 16, 14, 1, 2),  //  2  56x56 / 28x28: 16 waves, large chunks
-        FSCNN_V4P(16, 4, 4, 2, 8, 14, 1, 2),   //  3  14x14: whole image per tile, 2 channels per wave
-        FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),    //  4  64-wide rows
-        FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),     //  5  16 images per group
-        FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  //  6  two records per trip
-        FSCNN_V4X(32, 2, 2, 4, 16, 12, 1, 2),  //  7  32x4 tiles, 8 accumulators per channel, two groups per CU
-        FSCNN_V(1, 64, 1, 8, 8, 8, 8, 1, 2),   //  8  one image per lane (N < 4)
-        FSCNN_V(1, 32, 2, 8, 8, 8, 8, 1, 2),   //  9
-        FSCNN_V(1, 16, 4, 4, 8, 8, 8, 1, 2),   // 10
-        FSCNN_V(2, 64, 1, 4, 8, 8, 8, 2, 2),   // 11  two images per lane
+        FSCNN_V4P(32, 2, 4, 4, 8, 4, 1, 3),    //  1  wide, few-channel layers: 8 waves, small chunks
+        FSCNN_V4P(32, 2, 4, 4, 16, 14, 1, 2),  //  2  28x28: 16 waves, 4 channels each, large chunks
+        FSCNN_V4P(16, 4, 2, 2, 16, 24, 1, 2),  //  3  14x14: 16x8 tiles, 2 channels per wave
+        FSCNN_V4P(32, 2, 4, 2, 16, 7, 1, 2),   //  4  56x56 and up: 2 channels per wave, two groups per CU
+        FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),    //  5  64-wide rows
+        FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),     //  6  16 images per group
+        FSCNN_V4(16, 4, 4, 2, 8, 14, 1, 2),    //  7  16x16 tiles, 8 waves
+        FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  //  8  as 2, two records per trip
+        FSCNN_V4X(32, 2, 2, 4, 16, 11, 1, 2),  //  9  32x4 tiles, two groups per CU
+        FSCNN_V4X(32, 2, 2, 4, 16, 11, 2, 2),  // 10  as 9, two records per trip
+        FSCNN_V(1, 64, 1, 8, 8, 8, 8, 1, 2),   // 11  one image per lane (N < 4)
+        FSCNN_V(1, 32, 2, 8, 8, 8, 8, 1, 2),   // 12
+        FSCNN_V(1, 16, 4, 4, 8, 8, 8, 1, 2),   // 13
+        FSCNN_V(2, 64, 1, 4, 8, 8, 8, 2, 2),   // 14  two images per lane
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
@@ -601,26 +619,28 @@ static long long sf_blocks(const SfGeom &g, int N, int K, int Ho, int Wo)
 
 // Automatic choice.  Batches of at least four images use the image-interleaved (b128)
 // configurations.  Preference order measured on VGG16-shaped layers (N = 32, 95 % sparse):
-// 32x8 output tiles; 8-wave groups with small chunks for the wide, few-channel layers; 16-wave
-// groups (half the re-staging of the input) with the largest chunks LDS holds twice from 56x56
-// down (fewer barriers, more records per wave between them); whole-image 16x16 tiles with two
-// channels per wave for 14x14.  A configuration that would launch too few work-groups to
-// cover the 256 compute units yields to the next one with smaller groups.
+// 8-wave groups with small chunks for the wide layers with a handful of input channels; from
+// 224x224 down to 56x56, 16-wave groups of 2 channels per wave whose 64 registers and half-size
+// tiles let two groups share a CU (32 waves hide the LDS latency, and a group that waits at its
+// barrier leaves the CU to the other); at 28x28, 4 channels per wave with the largest chunks
+// LDS holds twice (fewer barriers, half the re-staging of the input); 16x8 tiles with two
+// channels per wave for 14x14, which keeps 256 groups of 16 waves in flight.  A configuration
+// that would launch too few work-groups to cover the 256 compute units yields to the next one.
 int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S)
 {
-    (void)C;
     if (R != 3 || S != 3) return 0;
     int n;
     const Variant *t = variants(&n);
     int pref[3];
     if (N >= 4) {
-        if (W > 64) { pref[0] = 1; pref[1] = 2; pref[2] = 3; }
-        else if (W > 16) { pref[0] = 2; pref[1] = 1; pref[2] = 3; }
-        else { pref[0] = 3; pref[1] = 3; pref[2] = 3; }
+        if (W > 64 && C <= 8) { pref[0] = 1; pref[1] = 4; pref[2] = 3; }
+        else if (W > 32) { pref[0] = 4; pref[1] = 2; pref[2] = 3; }
+        else if (W > 16) { pref[0] = 2; pref[1] = 4; pref[2] = 3; }
+        else { pref[0] = 3; pref[1] = 7; pref[2] = 7; }
     } else {
-        if (W > 32) { pref[0] = 8; pref[1] = 9; pref[2] = 10; }
-        else if (W > 16) { pref[0] = 9; pref[1] = 10; pref[2] = 10; }
-        else { pref[0] = 10; pref[1] = 10; pref[2] = 10; }
+        if (W > 32) { pref[0] = 11; pref[1] = 12; pref[2] = 13; }
+        else if (W > 16) { pref[0] = 12; pref[1] = 13; pref[2] = 13; }
+        else { pref[0] = 13; pref[1] = 13; pref[2] = 13; }
     }
     int best = pref[0];
     long long best_blocks = -1;
