@@ -120,7 +120,7 @@ fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan *
 // Which variant serves this geometry: `variant` > 0 is taken as is (checked), 0 = automatic,
 // anything the tiled kernel cannot do goes to the direct kernel (-1).
 fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int sh, int sw,
-                               int variant, int *resolved, bool n4 = false)
+                               int variant, int *resolved, bool n4 = false, bool pool = false)
 {
     // the tiled kernel addresses up to four images' channels with 32-bit byte offsets
     const bool tiled_ok = (sh == 1 && sw == 1) && (long long)f->C * H * W * 16 < 0x7ffffff0LL;
@@ -132,7 +132,7 @@ fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int
         return FSCNN_OK;
     }
     // N4 tensors need four images per lane whatever the batch size
-    int v = tiled_ok ? sf_choose_variant(n4 && N < 4 ? 4 : N, f->C, f->K, H, W, f->R, f->S) : 0;
+    int v = tiled_ok ? sf_choose_variant(n4 && N < 4 ? 4 : N, f->C, f->K, H, W, f->R, f->S, pool) : 0;
     *resolved = v > 0 ? v : -1;
     return FSCNN_OK;
 }
@@ -356,7 +356,7 @@ static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int 
         return FSCNN_ERR_UNSUPPORTED;
     if (pool && (Ho < 2 || Wo < 2)) return FSCNN_ERR_SHAPE;   // empty pooled output
     int v;
-    s = resolve_variant(f, N, H, W, sh, sw, variant, &v, in4 || out4);
+    s = resolve_variant(f, N, H, W, sh, sw, variant, &v, in4 || out4, pool != 0);
     if (s != FSCNN_OK) return s;
     if ((in4 || out4 || pool) && v < 0) return FSCNN_ERR_UNSUPPORTED;   // the direct kernel: NCHW, no pool
     if (v > 0 && !sf_variant_has_layout(v, in4, out4, pool)) return FSCNN_ERR_UNSUPPORTED;

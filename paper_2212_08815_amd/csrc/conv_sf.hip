@@ -558,13 +558,13 @@ const Variant *variants(int *count)
         FSCNN_V4P(32, 2, 4, 4, 8, 4, 1, 3),    //  1  wide, few-channel layers: 8 waves, small chunks
         FSCNN_V4P(32, 2, 4, 4, 16, 14, 1, 2),  //  2  28x28: 16 waves, 4 channels each, large chunks
         FSCNN_V4P(16, 4, 2, 2, 16, 24, 1, 2),  //  3  14x14: 16x8 tiles, 2 channels per wave
-        FSCNN_V4P(32, 2, 4, 2, 16, 7, 1, 2),   //  4  56x56 and up: 2 channels per wave, two groups per CU
-        FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),    //  5  64-wide rows
-        FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),     //  6  16 images per group
-        FSCNN_V4(16, 4, 4, 2, 8, 14, 1, 2),    //  7  16x16 tiles, 8 waves
-        FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  //  8  as 2, two records per trip
-        FSCNN_V4X(32, 2, 2, 4, 16, 11, 1, 2),  //  9  32x4 tiles, two groups per CU
-        FSCNN_V4X(32, 2, 2, 4, 16, 11, 2, 2),  // 10  as 9, two records per trip
+        FSCNN_V4P(32, 2, 4, 2, 16, 7, 1, 2),   //  4  56x56, 112x112: 2 channels per wave, two groups per CU
+        FSCNN_V4P(32, 2, 2, 4, 16, 11, 1, 2),  //  5  224x224: 32x4 tiles, two groups per CU
+        FSCNN_V4(32, 2, 7, 2, 16, 7, 1, 2),    //  6  32x14 tiles: heights 28 and 56 without idle rows
+        FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),    //  7  64-wide rows
+        FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),     //  8  16 images per group
+        FSCNN_V4(16, 4, 4, 2, 8, 14, 1, 2),    //  9  16x16 tiles, 8 waves
+        FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  // 10  as 2, two records per trip
         FSCNN_V(1, 64, 1, 8, 8, 8, 8, 1, 2),   // 11  one image per lane (N < 4)
         FSCNN_V(1, 32, 2, 8, 8, 8, 8, 1, 2),   // 12
         FSCNN_V(1, 16, 4, 4, 8, 8, 8, 1, 2),   // 13
@@ -620,32 +620,46 @@ static long long sf_blocks(const SfGeom &g, int N, int K, int Ho, int Wo)
 // Automatic choice.  Batches of at least four images use the image-interleaved (b128)
 // configurations.  Preference order measured on VGG16-shaped layers (N = 32, 95 % sparse):
 // 8-wave groups with small chunks for the wide layers with a handful of input channels; from
-// 224x224 down to 56x56, 16-wave groups of 2 channels per wave whose 64 registers and half-size
-// tiles let two groups share a CU (32 waves hide the LDS latency, and a group that waits at its
-// barrier leaves the CU to the other); at 28x28, 4 channels per wave with the largest chunks
-// LDS holds twice (fewer barriers, half the re-staging of the input); 16x8 tiles with two
-// channels per wave for 14x14, which keeps 256 groups of 16 waves in flight.  A configuration
-// that would launch too few work-groups to cover the 256 compute units yields to the next one.
-int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S)
+// 224x224 down to 56x56, 16-wave groups whose 64 registers and half-size tiles let two groups
+// share a CU (32 waves hide the LDS latency, and a group that waits at its barrier leaves the
+// CU to the other); at 56x56 and 28x28 without pooling, 32x14 tiles (7 rows per lane: no idle
+// rows for heights 28 and 56, and 28 multiply-adds per record fetched); at 28x28 with pooling,
+// 4 channels per wave with the largest chunks LDS holds twice; 16x8 tiles with two channels
+// per wave for 14x14, which keeps 256 groups of 16 waves in flight.  A configuration that
+// would launch too few work-groups to cover the 256 compute units, or that has no pooled form
+// when one is asked for, yields to the next one.
+int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, bool pool)
 {
     if (R != 3 || S != 3) return 0;
     int n;
     const Variant *t = variants(&n);
-    int pref[3];
+    int pref[4];
     if (N >= 4) {
-        if (W > 64 && C <= 8) { pref[0] = 1; pref[1] = 4; pref[2] = 3; }
-        else if (W > 32) { pref[0] = 4; pref[1] = 2; pref[2] = 3; }
-        else if (W > 16) { pref[0] = 2; pref[1] = 4; pref[2] = 3; }
-        else { pref[0] = 3; pref[1] = 7; pref[2] = 7; }
+        if (W > 64 && C <= 8) { pref[0] = 1; pref[1] = 4; pref[2] = 3; pref[3] = 3; }
+        else if (W > 128) { pref[0] = 5; pref[1] = 4; pref[2] = 2; pref[3] = 3; }
+        else if (W > 64) { pref[0] = 4; pref[1] = 2; pref[2] = 3; pref[3] = 3; }
+        else if (W > 32) { pref[0] = 6; pref[1] = 4; pref[2] = 2; pref[3] = 3; }
+        else if (W > 16) { pref[0] = 6; pref[1] = 2; pref[2] = 4; pref[3] = 3; }
+        else { pref[0] = 3; pref[1] = 9; pref[2] = 9; pref[3] = 9; }
     } else {
-        if (W > 32) { pref[0] = 11; pref[1] = 12; pref[2] = 13; }
-        else if (W > 16) { pref[0] = 12; pref[1] = 13; pref[2] = 13; }
-        else { pref[0] = 13; pref[1] = 13; pref[2] = 13; }
+        if (W > 32) { pref[0] = 11; pref[1] = 12; pref[2] = 13; pref[3] = 13; }
+        else if (W > 16) { pref[0] = 12; pref[1] = 13; pref[2] = 13; pref[3] = 13; }
+        else { pref[0] = 13; pref[1] = 13; pref[2] = 13; pref[3] = 13; }
     }
-    int best = pref[0];
+    // the 14-row tiles do not pay where they waste more rows than the 8-row ones
+    auto covered = [&](const SfGeom &g) {
+        return (long long)((W + g.TW - 1) / g.TW) * g.TW * ((H + g.TH - 1) / g.TH) * g.TH;
+    };
+    if (pref[0] == 6 && covered(t[5].g) > covered(t[pref[1] - 1].g)) {
+        pref[0] = pref[1];
+        pref[1] = 6;
+    }
+    int best = 0;
     long long best_blocks = -1;
-    for (int i = 0; i < 3; ++i) {
-        const long long b = sf_blocks(t[pref[i] - 1].g, N, K, H, W);  // Ho, Wo ~ H, W for this purpose
+    for (int i = 0; i < 4; ++i) {
+        const Variant &v = t[pref[i] - 1];
+        if (pool && !v.pool[0][0]) continue;
+        const long long b = sf_blocks(v.g, N, K, H, W);  // Ho, Wo ~ H, W for this purpose
         if (b >= 192) return pref[i];
         if (b > best_blocks) { best_blocks = b; best = pref[i]; }
     }
