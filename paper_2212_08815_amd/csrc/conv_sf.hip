@@ -48,8 +48,11 @@ struct Cfg {
     static_assert((!IN4 && !OUT4) || BV == 4, "N4 tensors need four images per lane");
     static constexpr int IG = 64 / (LW * LHR);   // image groups across the lanes of a wave
     static_assert(IG * LW * LHR == 64, "lanes must factor as LW * LHR * IG");
-    // U records per trip of the inner loop: their taps are read together, then multiplied
-    static_assert(U == 1 || U == 2 || U == 4, "records per trip");
+    // U = 1, 2, 4: U records per trip of the inner loop, their taps read together, then
+    // multiplied; U = 0: software-pipelined loop (the next record's taps are read while the
+    // current one is multiplied)
+    static_assert(U == 0 || U == 1 || U == 2 || U == 4, "records per trip");
+    static_assert(U != 0 || BV == 4, "the pipelined loop is written for four images per lane");
     static constexpr int IMGS = BV * IG;         // images per work-group
     static constexpr int P = NV * BV;            // accumulators per lane and channel
     static constexpr int TH = LHR * NV, TW = LW; // output tile
@@ -90,7 +93,7 @@ struct Cfg {
     static constexpr int NT = WAVES * 64;
     static constexpr int NIW = (NI + WAVES - 1) / WAVES;   // lines per wave and image group
     static constexpr int ROWSTEP = PITCH * BV * 4;         // bytes from one tile row to the next
-    static constexpr int FIFO = U;                         // records held ahead in SGPRs
+    static constexpr int FIFO = U == 0 ? 3 : U;            // records held ahead in SGPRs
     // loads a wave may leave in flight once the NEXT chunk has to be complete: every wave
     // issues at least IG*(NI/WAVES) lines per chunk, and D-1 younger chunks follow it
     static constexpr int WAITN = (D - 1) * IG * (NI / WAVES) > 63 ? 63 : (D - 1) * IG * (NI / WAVES);
@@ -99,7 +102,7 @@ struct Cfg {
     // registers of addressing (512 vector registers per SIMD lane, 4 SIMDs per CU).
     static constexpr int pick_wpe()
     {
-        const int need = P * SLOTS + U * P + 24;
+        const int need = P * SLOTS + (U == 0 ? 2 : U) * P + 24;
         for (int g = 160 * 1024 / LDS_BYTES; g > 1; --g) {
             const int w = (g * WAVES + 3) / 4;
             if (w <= 8 && 512 / w >= need) return w;
@@ -285,6 +288,77 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
         rbuf = rbuf + 1 == G::NB ? 0 : rbuf + 1;
 
         // ---- gather-FMA over this wave's records of the chunk (A5)
+        if constexpr (G::U == 0) {
+            // Software pipeline (BV = 4).  Invariant at the top of a trip for record i:
+            // q[0..2] = records i, i+1, i+2 and the taps of record i are in flight into `cur`.
+            // A trip waits for them (and for the record fetched one trip ago), starts the reads
+            // of record i+1 into the other buffer and the fetch of record i+3, and only then
+            // multiplies record i: the LDS latency hides behind the multiply-adds of the same
+            // wave.  Trips come in pairs (A then B), so every segment starts with its first
+            // record in buffer A; a segment's odd last record is multiplied out of A and only
+            // then are the next record's reads issued into A again.  Reads that run past the
+            // chunk's last record fetch a valid tap of this chunk's tile and are issued again
+            // after the barrier.  The empty statement that names the taps makes the compiler
+            // place its wait there, before the next reads, and the scheduling barriers keep
+            // that order.
+            f4v tapA[G::NV], tapB[G::NV];
+            auto issue = [&](f4v(&dst)[G::NV], uint32_t off) {
+                const char *p = tile + off;
+#pragma unroll
+                for (int v = 0; v < G::NV; ++v) dst[v] = *reinterpret_cast<const f4v *>(p + v * G::ROWSTEP);
+            };
+            auto landed = [&](f4v(&buf)[G::NV]) {
+#pragma unroll
+                for (int v = 0; v < G::NV; ++v) asm volatile("" : : "v"(buf[v]));
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            issue(tapA, q[0].off);
+#pragma unroll
+            for (int j = 0; j < G::SLOTS; ++j) {
+                if (more) fetch(ci + G::D, wbuf, j, G::SLOTS);
+                const int end = bnd[j];
+                auto mul = [&](f4v(&cur)[G::NV]) {
+#pragma unroll
+                    for (int v = 0; v < G::NV; ++v) {
+                        acc[j][v * 4 + 0] = __builtin_fmaf(q[0].val, cur[v].x, acc[j][v * 4 + 0]);
+                        acc[j][v * 4 + 1] = __builtin_fmaf(q[0].val, cur[v].y, acc[j][v * 4 + 1]);
+                        acc[j][v * 4 + 2] = __builtin_fmaf(q[0].val, cur[v].z, acc[j][v * 4 + 2]);
+                        acc[j][v * 4 + 3] = __builtin_fmaf(q[0].val, cur[v].w, acc[j][v * 4 + 3]);
+                    }
+                };
+                auto trip = [&](f4v(&cur)[G::NV], f4v(&nxt)[G::NV]) {
+                    landed(cur);
+                    issue(nxt, q[1].off);
+                    const Rec fresh = recs[i + 3];
+                    __builtin_amdgcn_sched_barrier(0);
+                    mul(cur);
+                    q[0] = q[1];
+                    q[1] = q[2];
+                    q[2] = fresh;
+                    ++i;
+                    __builtin_amdgcn_sched_barrier(0);
+                };
+                while (i + 1 < end) {
+                    trip(tapA, tapB);
+                    trip(tapB, tapA);
+                }
+                if (i < end) {  // odd tail
+                    landed(tapA);
+                    const Rec fresh = recs[i + 3];
+                    mul(tapA);
+                    __builtin_amdgcn_sched_barrier(0);
+                    issue(tapA, q[1].off);
+                    q[0] = q[1];
+                    q[1] = q[2];
+                    q[2] = fresh;
+                    ++i;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            // the read in flight targets this chunk's buffer: let it land before the barrier
+            // below allows that buffer to be overwritten
+            landed(tapA);
+        } else
 #pragma unroll
         for (int j = 0; j < G::SLOTS; ++j) {
             if (more) fetch(ci + G::D, wbuf, j, G::SLOTS);
@@ -556,19 +630,21 @@ const Variant *variants(int *count)
 {
     static const Variant table[] = {
         FSCNN_V4P(32, 2, 4, 4, 8, 4, 1, 3),    //  1  wide, few-channel layers: 8 waves, small chunks
-        FSCNN_V4P(32, 2, 4, 4, 16, 14, 1, 2),  //  2  28x28: 16 waves, 4 channels each, large chunks
+        FSCNN_V4P(32, 2, 4, 4, 16, 14, 0, 2),  //  2  28x28, 56x56 with pooling: 16 waves, 4 channels each, large chunks, pipelined
         FSCNN_V4P(16, 4, 2, 2, 16, 24, 1, 2),  //  3  14x14: 16x8 tiles, 2 channels per wave
-        FSCNN_V4P(32, 2, 4, 2, 16, 7, 1, 2),   //  4  56x56, 112x112: 2 channels per wave, two groups per CU
+        FSCNN_V4P(32, 2, 4, 2, 16, 7, 1, 2),   //  4  112x112: 2 channels per wave, two groups per CU
         FSCNN_V4P(32, 2, 2, 4, 16, 11, 1, 2),  //  5  224x224: 32x4 tiles, two groups per CU
-        FSCNN_V4(32, 2, 7, 2, 16, 7, 1, 2),    //  6  32x14 tiles: heights 28 and 56 without idle rows
+        FSCNN_V4(32, 2, 7, 2, 16, 7, 0, 2),    //  6  32x14 tiles: heights 28 and 56 without idle rows, pipelined
         FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),    //  7  64-wide rows
         FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),     //  8  16 images per group
         FSCNN_V4(16, 4, 4, 2, 8, 14, 1, 2),    //  9  16x16 tiles, 8 waves
-        FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  // 10  as 2, two records per trip
+        FSCNN_V4X(32, 2, 4, 4, 16, 14, 1, 2),  // 10  as 2, not pipelined
         FSCNN_V(1, 64, 1, 8, 8, 8, 8, 1, 2),   // 11  one image per lane (N < 4)
         FSCNN_V(1, 32, 2, 8, 8, 8, 8, 1, 2),   // 12
         FSCNN_V(1, 16, 4, 4, 8, 8, 8, 1, 2),   // 13
         FSCNN_V(2, 64, 1, 4, 8, 8, 8, 2, 2),   // 14  two images per lane
+        FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  // 15  as 2, two records per trip
+        FSCNN_V4X(32, 2, 7, 2, 16, 7, 1, 2),   // 16  as 6, not pipelined
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
@@ -623,9 +699,9 @@ static long long sf_blocks(const SfGeom &g, int N, int K, int Ho, int Wo)
 // 224x224 down to 56x56, 16-wave groups whose 64 registers and half-size tiles let two groups
 // share a CU (32 waves hide the LDS latency, and a group that waits at its barrier leaves the
 // CU to the other); at 56x56 and 28x28 without pooling, 32x14 tiles (7 rows per lane: no idle
-// rows for heights 28 and 56, and 28 multiply-adds per record fetched); at 28x28 with pooling,
-// 4 channels per wave with the largest chunks LDS holds twice; 16x8 tiles with two channels
-// per wave for 14x14, which keeps 256 groups of 16 waves in flight.  A configuration that
+// rows for heights 28 and 56, and 28 multiply-adds per record fetched) with the pipelined
+// loop; with pooling, 4 channels per wave with the largest chunks LDS holds twice, pipelined;
+// 16x8 tiles with two channels per wave for 14x14, which keeps 256 groups of 16 waves in flight.  A configuration that
 // would launch too few work-groups to cover the 256 compute units, or that has no pooled form
 // when one is asked for, yields to the next one.
 int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, bool pool)
@@ -638,7 +714,7 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, bool pool
         if (W > 64 && C <= 8) { pref[0] = 1; pref[1] = 4; pref[2] = 3; pref[3] = 3; }
         else if (W > 128) { pref[0] = 5; pref[1] = 4; pref[2] = 2; pref[3] = 3; }
         else if (W > 64) { pref[0] = 4; pref[1] = 2; pref[2] = 3; pref[3] = 3; }
-        else if (W > 32) { pref[0] = 6; pref[1] = 4; pref[2] = 2; pref[3] = 3; }
+        else if (W > 32) { pref[0] = 6; pref[1] = 2; pref[2] = 4; pref[3] = 3; }
         else if (W > 16) { pref[0] = 6; pref[1] = 2; pref[2] = 4; pref[3] = 3; }
         else { pref[0] = 3; pref[1] = 9; pref[2] = 9; pref[3] = 9; }
     } else {
