@@ -44,7 +44,8 @@ struct Cfg {
     // POOL: the epilogue also applies the 2x2 / stride-2 max-pool (merged convolution and
     // pooling, Alg. 7) and stores the pooled tensor only
     static constexpr bool POOL = POOL_;
-    static_assert(!POOL || (NV_ % 2 == 0 && LW_ % 2 == 0), "pooling pairs rows inside a lane and columns of lane pairs");
+    static_assert(!POOL || (LW_ % 2 == 0 && (NV_ % 2 == 0 || (LW_ == 32 && LHR_ == 2))),
+                  "pooling pairs columns of lane pairs and rows inside a lane (odd NV: also across lanes l, l^32)");
     static_assert((!IN4 && !OUT4) || BV == 4, "N4 tensors need four images per lane");
     static constexpr int IG = 64 / (LW * LHR);   // image groups across the lanes of a wave
     static_assert(IG * LW * LHR == 64, "lanes must factor as LW * LHR * IG");
@@ -57,16 +58,20 @@ struct Cfg {
     static constexpr int P = NV * BV;            // accumulators per lane and channel
     static constexpr int TH = LHR * NV, TW = LW; // output tile
     static constexpr int IN_ROWS = TH + R - 1;
-    // LDS serves a wide read of lane i together with lane i+32 (measured: the 16x4 lane shape
-    // showed a 50 % bank-conflict rate, the 32x2 shape none), so the byte offset of lane 32's
-    // vector must be 128 modulo 256; where lane 32 starts another row group the row pitch is
-    // padded until that holds.  (With 64 lanes in one row, or lane 32 in another image group,
-    // the offset is fixed by the layout.)
+    // Bank conflicts of the 16-byte LDS reads, measured on gfx950 with per-lane offsets: a wave
+    // whose lanes 0-31 and 32-63 each read 512 contiguous bytes is conflict-free wherever the
+    // two halves lie; with four groups of 16 lanes (256 contiguous bytes each) the read is
+    // conflict-free only if groups 0 and 1 are a multiple of 256 bytes apart and so are groups
+    // 2 and 3 (otherwise it takes twice as long).  For LW = 16, LHR = 4 the lane groups are
+    // therefore given the row groups 0, 2, 1, 3 (where the kernel derives lh) and the pitch is padded
+    // until two row groups are a multiple of 256 bytes apart; for LW = 16, LHR = 2 until one is.
     static constexpr int pick_pitch()
     {
         int p = TW + S - 1;
-        if (LW < 64 && LHR > 1 && BV * 4 == 16)
-            while ((((32 / LW) * NV * p * 16) % 256) != 128 && p < TW + S - 1 + 16) ++p;
+        if (LW == 16 && BV * 4 == 16 && LHR == 4)
+            while ((2 * NV * p * 16) % 256 != 0) ++p;
+        if (LW == 16 && BV * 4 == 16 && LHR == 2)
+            while ((NV * p * 16) % 256 != 0) ++p;
         return p;
     }
     static constexpr int PITCH = pick_pitch();
@@ -75,15 +80,9 @@ struct Cfg {
     // one staging load fills an LDS line of 64 dwords (NCHW input) or 64 BV-vectors (N4 input)
     static constexpr int LINE_BYTES = IN4 ? 1024 : 256;
     static constexpr int NI = IN4 ? (IG_ELEMS + 63) / 64 : (IG_DW + 63) / 64;  // lines per image group
-    // padded so that a line never spills; where lane 32 belongs to another image group the
-    // group stride is nudged so that lane 32 sits 128 bytes (mod 256) from lane 0 (see PITCH)
-    static constexpr int pick_ig_bytes()
-    {
-        int b = NI * LINE_BYTES;
-        if (LW * LHR <= 32 && BV * 4 == 16)
-            while ((((32 / (LW * LHR)) * b) % 256) != 128) b += 16;
-        return b;
-    }
+    // padded so that a line never spills (a multiple of 256 bytes, which is also what the
+    // lane groups of different image groups need to stay conflict-free)
+    static constexpr int pick_ig_bytes() { return NI * LINE_BYTES; }
     static constexpr int IG_BYTES = pick_ig_bytes();
     static constexpr int BUF_BYTES = IG * IG_BYTES;
     static constexpr int LDS_BYTES = NB * BUF_BYTES;
@@ -196,7 +195,9 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lx = lane % G::LW;
-    const int lh = (lane / G::LW) % G::LHR;
+    const int lg = (lane / G::LW) % G::LHR;
+    // row group of this lane group: 0, 2, 1, 3 for four groups of 16 lanes (see PITCH)
+    const int lh = (G::LW == 16 && G::LHR == 4) ? (((lg & 1) << 1) | (lg >> 1)) : lg;
     const int ig = lane / (G::LW * G::LHR);
     const uint32_t lane_base = (uint32_t)(ig * G::IG_BYTES + ((lh * G::NV) * G::PITCH + lx) * G::BV * 4);
 
@@ -420,7 +421,11 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     const int ox = tx0 + lx;
     if constexpr (G::POOL) {
         // merged 2x2 max-pool: rows pair up inside a lane (tile rows start even), columns across
-        // the lane pair (lx, lx^1); adding the bias and the ReLU commute with the maximum
+        // the lane pair (lx, lx^1); adding the bias and the ReLU commute with the maximum.
+        // With an odd number of rows per lane (32x2 lanes only) the second row group starts on
+        // an odd row: its pairs are shifted by one, and the pair that straddles the two groups
+        // is completed across lanes l and l^32 and stored by the first group.
+        constexpr bool ODD = G::NV % 2 != 0;
         const int Hp = Ho / 2, Wp = Wo / 2;
         const long long pplane = (long long)Hp * Wp;
         const int px = ox >> 1;
@@ -429,21 +434,18 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
             const int k = kg * G::KG + wave * G::SLOTS + j;
             if (k >= K) break;
             const float bk = bias ? bias[k] : 0.0f;
-#pragma unroll
-            for (int v = 0; v < G::NV; v += 2) {
-                const int py = (ty0 + lh * G::NV + v) >> 1;
+            auto put = [&](int py, const float *a0, const float *a1, bool writer) {
                 float r[G::BV];
 #pragma unroll
                 for (int b = 0; b < G::BV; ++b) {
-                    const float a0 = acc[j][v * G::BV + b], a1 = acc[j][(v + 1) * G::BV + b];
-                    float m = a1 > a0 ? a1 : a0;
+                    float m = a1[b] > a0[b] ? a1[b] : a0[b];
                     const float o = __shfl_xor(m, 1, 64);
                     m = o > m ? o : m;
                     m += bk;
                     if (relu) m = m > 0.0f ? m : 0.0f;
                     r[b] = m;
                 }
-                const bool ok = (lx & 1) == 0 && py < Hp && px < Wp;
+                const bool ok = writer && (lx & 1) == 0 && py < Hp && px < Wp;
                 if constexpr (G::OUT4) {
                     const int n = n0 + ig * 4;
                     if (ok && n < N)
@@ -457,6 +459,30 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                         if (ok && n < N) y[((long long)n * K + k) * pplane + (long long)py * Wp + px] = r[b];
                     }
                 }
+            };
+            if constexpr (!ODD) {
+#pragma unroll
+                for (int v = 0; v < G::NV; v += 2)
+                    put((ty0 + lh * G::NV + v) >> 1, &acc[j][v * G::BV], &acc[j][(v + 1) * G::BV], true);
+            } else {
+                const bool second = lh != 0;  // rows NV .. 2*NV-1 of the tile: pairs start at local row 1
+#pragma unroll
+                for (int v = 0; v + 1 < G::NV; v += 2) {
+                    float a0[G::BV], a1[G::BV];
+#pragma unroll
+                    for (int b = 0; b < G::BV; ++b) {
+                        a0[b] = second ? acc[j][(v + 1) * G::BV + b] : acc[j][v * G::BV + b];
+                        a1[b] = second ? acc[j][(v + 2) * G::BV + b] : acc[j][(v + 1) * G::BV + b];
+                    }
+                    put((ty0 + lh * G::NV + v + (second ? 1 : 0)) >> 1, a0, a1, true);
+                }
+                float mine[G::BV], other[G::BV];
+#pragma unroll
+                for (int b = 0; b < G::BV; ++b) {
+                    mine[b] = second ? acc[j][b] : acc[j][(G::NV - 1) * G::BV + b];
+                    other[b] = __shfl_xor(mine[b], 32, 64);
+                }
+                put((ty0 + G::NV - 1) >> 1, mine, other, !second);
             }
         }
         return;
@@ -633,8 +659,8 @@ const Variant *variants(int *count)
         FSCNN_V4P(32, 2, 4, 4, 16, 14, 0, 2),  //  2  28x28, 56x56 with pooling: 16 waves, 4 channels each, large chunks, pipelined
         FSCNN_V4P(16, 4, 2, 2, 16, 24, 1, 2),  //  3  14x14: 16x8 tiles, 2 channels per wave
         FSCNN_V4P(32, 2, 4, 2, 16, 7, 1, 2),   //  4  112x112: 2 channels per wave, two groups per CU
-        FSCNN_V4P(32, 2, 2, 4, 16, 11, 1, 2),  //  5  224x224: 32x4 tiles, two groups per CU
-        FSCNN_V4(32, 2, 7, 2, 16, 7, 0, 2),    //  6  32x14 tiles: heights 28 and 56 without idle rows, pipelined
+        FSCNN_V4P(32, 2, 2, 4, 16, 12, 1, 2),  //  5  224x224: 32x4 tiles, two groups per CU
+        FSCNN_V4P(32, 2, 7, 2, 16, 9, 0, 2),   //  6  32x14 tiles: heights 28 and 56 without idle rows, pipelined
         FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),    //  7  64-wide rows
         FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),     //  8  16 images per group
         FSCNN_V4(16, 4, 4, 2, 8, 14, 1, 2),    //  9  16x16 tiles, 8 waves
@@ -644,7 +670,7 @@ const Variant *variants(int *count)
         FSCNN_V(1, 16, 4, 4, 8, 8, 8, 1, 2),   // 13
         FSCNN_V(2, 64, 1, 4, 8, 8, 8, 2, 2),   // 14  two images per lane
         FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  // 15  as 2, two records per trip
-        FSCNN_V4X(32, 2, 7, 2, 16, 7, 1, 2),   // 16  as 6, not pipelined
+        FSCNN_V4X(32, 2, 7, 2, 16, 9, 1, 2),   // 16  as 6, not pipelined
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
