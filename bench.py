@@ -6,10 +6,16 @@ stack of 13 3x3 convolution layers (channels 64-64-128-128-256x3-512x3-512x3, 2x
 between blocks), batch N=32, 224x224x3 fp32 input ~U[0,1), 95 % random unstructured weight
 sparsity on every layer but the first (dense), bias + ReLU fused into each convolution.
 
-A "step" is one pass of the whole stack over one batch: 13 fscnn_conv2d_sparse_filter launches
-plus the 4 helper max-pools, input and compressed filters already resident in HBM.  The first
-layer reads NCHW, the last writes NCHW, the layers in between hand each other N4
-(batch-interleaved) tensors.  Effective work is F_eff = sum over layers of 2*nnz*Ho*Wo*N.
+A "step" is one pass of the whole stack over one batch: 13 convolution launches, input and
+compressed filters already resident in HBM.  The 2x2 max-pools that follow layers 2, 4, 7, 10
+(and 13) are merged into those layers' launches (merged convolution + pooling, Alg. 7);
+`--separate-pool` runs them as helper kernels instead.  The first layer reads NCHW, the last
+writes NCHW, the layers in between hand each other N4 (batch-interleaved) tensors.  Effective
+work is F_eff = sum over layers of 2*nnz*Ho*Wo*N.
+
+The `roofline` object describes the dominant kernel: the kernel instantiation (configuration,
+layouts, pooled or not) with the largest share of the step.  Its launch duration is the mean over
+its launches (several layers may share it), measured with HIP events inside the timed region.
 
 Prints ONE JSON line (see the keys below).  `--gpus N` with N > 1 is refused: this build runs
 on one GPU.
@@ -205,12 +211,20 @@ def main():
     alloc_buffers(fscnn, torch, dev_layers, n, not args.separate_pool)
 
     # per-layer effective work and algorithmic bytes (x read once, y written once, compressed filter
-    # and bias read once)
-    feff, balg = [], []
+    # and bias read once).  balg follows the per-convolution definition (full-size y) and feeds the
+    # stack's HBM figure; blaunch counts what the launch itself has to move, i.e. the pooled tensor
+    # where the pool is merged into the launch, and feeds the per-kernel figures.
+    feff, balg, blaunch, kern = [], [], [], []
     for d in dev_layers:
         hw = d["hw"]
         feff.append(2.0 * d["f"].nnz * hw * hw * n)
-        balg.append(4.0 * n * hw * hw * (d["c"] + d["k"]) + 8.0 * d["f"].nnz + 4.0 * (d["k"] + 1) + 4.0 * d["k"])
+        fixed = 8.0 * d["f"].nnz + 4.0 * (d["k"] + 1) + 4.0 * d["k"]
+        balg.append(4.0 * n * hw * hw * (d["c"] + d["k"]) + fixed)
+        yhw = (hw // 2) * (hw // 2) if d["fused"] else hw * hw
+        blaunch.append(4.0 * n * (hw * hw * d["c"] + yhw * d["k"]) + fixed)
+        v = fscnn.sf_variant_choice(d["f"], n, hw, hw, n4=(d["lay_in"] == fscnn.N4 or d["lay_out"] == fscnn.N4),
+                                    pool=d["fused"])
+        kern.append((fscnn.sf_variant_name(v) if v > 0 else "direct", d["lay_in"], d["lay_out"], d["fused"]))
     F, B = sum(feff), sum(balg)
 
     for _ in range(max(args.warmup, 1)):       # also builds every plan: the timed loop allocates nothing
@@ -231,18 +245,28 @@ def main():
     layer_ms = [float(np.mean([events[s][li][0].elapsed_time(events[s][li][1]) for s in range(args.steps)]))
                 for li in range(len(dev_layers))]
     conv_ms = sum(layer_ms)
-    # dominant kernel = the layer launch with the largest share of the step
-    dom = int(np.argmax(layer_ms))
-    dd = dev_layers[dom]
-    dom_tflops = feff[dom] / (layer_ms[dom] * 1e-3) / 1e12
+    # dominant kernel = the instantiation (configuration, layouts, pooled or not) with the largest
+    # share of the step; its figures are means over its launches
+    share = {}
+    for li, kid in enumerate(kern):
+        share.setdefault(kid, []).append(li)
+    dom_id = max(share, key=lambda kid: sum(layer_ms[li] for li in share[kid]))
+    dom = share[dom_id]
+    dom_ms = float(np.mean([layer_ms[li] for li in dom]))
+    dom_flop = float(np.mean([feff[li] for li in dom]))
+    dom_bytes = float(np.mean([blaunch[li] for li in dom]))
+    dom_tflops = dom_flop / (dom_ms * 1e-3) / 1e12
+    lay = {fscnn.NCHW: "NCHW", fscnn.N4: "N4"}
     roofline = dict(bound="alu", achieved=dom_tflops, peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=dom_tflops / FP32_VECTOR_PEAK_TFLOPS, traffic=None,
-                    kernel="conv_sf_tiled_kernel, layer %d (C=%d K=%d %dx%d N=%d, nnz=%d)" % (
-                        dom + 1, dd["c"], dd["k"], dd["hw"], dd["hw"], n, dd["f"].nnz),
-                    launch_ms=layer_ms[dom], flop_per_launch=feff[dom], bytes_per_launch=balg[dom],
+                    kernel="conv_sf_tiled_kernel %s %s->%s%s, layers %s" % (
+                        dom_id[0], lay[dom_id[1]], lay[dom_id[2]], " +pool" if dom_id[3] else "",
+                        ",".join(str(li + 1) for li in dom)),
+                    launches_per_step=len(dom), launch_ms=dom_ms, flop_per_launch=dom_flop,
+                    bytes_per_launch=dom_bytes,
                     peak_unpacked=FP32_UNPACKED_PEAK_TFLOPS, frac_unpacked=dom_tflops / FP32_UNPACKED_PEAK_TFLOPS,
-                    hbm_gbs=balg[dom] / (layer_ms[dom] * 1e-3) / 1e9,
-                    hbm_frac=balg[dom] / (layer_ms[dom] * 1e-3) / 1e9 / HBM_PEAK_GBS)
+                    hbm_gbs=dom_bytes / (dom_ms * 1e-3) / 1e9,
+                    hbm_frac=dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS)
     # measured HBM bytes of that launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy
     # kernel of known size): taken from the committed summary of the same workload, else null
     # what the chip sustains on the hot loop's instruction mix alone (one LDS word per FMA)
@@ -251,10 +275,13 @@ def main():
     roofline["frac_of_measured_ceiling"] = dom_tflops / ceiling
     traffic_file = os.path.join(ROOT, "profiles", "conv_sf_vgg16_n32_hbm_traffic.txt")
     if os.path.exists(traffic_file) and n == 32 and abs(args.keep - 0.05) < 1e-9:
+        per_layer = {}
         for line in open(traffic_file):
             f = line.split()
-            if len(f) == 4 and f[0] == "layer_%d" % (dom + 1):
-                roofline["traffic"] = float(f[3])
+            if len(f) == 4 and f[0].startswith("layer_"):
+                per_layer[int(f[0][6:]) - 1] = float(f[3])
+        if all(li in per_layer for li in dom):
+            roofline["traffic"] = float(np.mean([per_layer[li] for li in dom]))
 
     out = dict(
         metric="effective GFLOP/s (2*nnz*Ho*Wo*N) + HBM GB/s fraction, VGG16-shaped stack @95%",
@@ -264,6 +291,7 @@ def main():
         config=dict(workload="VGG16 conv stack, 13 layers 3x3 s1 p1 + 4 max-pools, N=%d, 224x224x3, "
                              "weight density %.2f (first layer dense), bias+ReLU fused" % (n, args.keep),
                     batch=n, effective_gflop_per_step=F / 1e9, algorithmic_gbytes_per_step=B / 1e9,
+                    launched_gbytes_per_step=sum(blaunch) / 1e9,
                     nnz_total=int(sum(d["f"].nnz for d in dev_layers))),
         hbm=dict(algorithmic_gbs=B / (ms_per_step * 1e-3) / 1e9,
                  frac_of_peak=B / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, peak_gbs=HBM_PEAK_GBS),

@@ -119,6 +119,15 @@ fscnn_status_t fscnn_filter_destroy(fscnn_filter_t *f);
 int fscnn_sf_variant_count(void);
 const char *fscnn_sf_variant_name(int variant);
 
+/* Which kernel configuration the automatic choice (variant 0) takes for this filter and
+ * geometry: *variant_out receives its id (1..count), or -1 when the untiled direct kernel
+ * serves the geometry.  `n4` is nonzero if the input or the output tensor is in the N4
+ * layout, `pool` if the merged 2x2 max-pool epilogue is asked for.  Host-only: launches
+ * nothing and needs no device. */
+fscnn_status_t fscnn_sf_variant_choice(const fscnn_filter_t *f, int N, int H, int W,
+                                       int stride_h, int stride_w, int n4, int pool,
+                                       int *variant_out);
+
 /* Sparse-filter convolution (Alg. 6: every output element, all filters; inner product of
  * Alg. 2 over the stored nonzeros only; no kernel flip; padding as index shift):
  *   y[n,k,oy,ox] = sum over stored (c,r,s,v) of filter k of

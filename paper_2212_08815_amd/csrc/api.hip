@@ -338,6 +338,15 @@ fscnn_status_t fscnn_filter_destroy(fscnn_filter_t *f)
 int fscnn_sf_variant_count(void) { return sf_variant_count(); }
 const char *fscnn_sf_variant_name(int variant) { return sf_variant_name(variant); }
 
+fscnn_status_t fscnn_sf_variant_choice(const fscnn_filter_t *f, int N, int H, int W, int sh, int sw,
+                                       int n4, int pool, int *variant_out)
+{
+    if (!f || !variant_out) return FSCNN_ERR_NULL;
+    if (!live(f)) return FSCNN_ERR_HANDLE;
+    if (N <= 0 || H <= 0 || W <= 0 || sh <= 0 || sw <= 0) return FSCNN_ERR_SHAPE;
+    return resolve_variant(f, N, H, W, sh, sw, 0, variant_out, n4 != 0, pool != 0);
+}
+
 static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int N, int C, int H,
                                      int W, int sh, int sw, int ph, int pw, const float *bias_dev,
                                      int relu, float *y_dev, fscnn_layout_t x_layout,

@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_MISMATCH", 4: "E
 EXPORTS = [
     "fscnn_status_string", "fscnn_conv2d_out_shape", "fscnn_filter_compress", "fscnn_filter_info",
     "fscnn_filter_export", "fscnn_filter_prepare", "fscnn_filter_plan_export",
-    "fscnn_filter_destroy", "fscnn_sf_variant_count", "fscnn_sf_variant_name",
+    "fscnn_filter_destroy", "fscnn_sf_variant_count", "fscnn_sf_variant_name", "fscnn_sf_variant_choice",
     "fscnn_conv2d_sparse_filter", "fscnn_conv2d_sparse_filter_v", "fscnn_input_compress",
     "fscnn_input_info", "fscnn_input_export", "fscnn_input_destroy", "fscnn_conv2d_sparse_input",
     "fscnn_maxpool2x2", "fscnn_conv2d_sparse_filter_ex", "fscnn_layout_convert",
@@ -100,6 +100,15 @@ def sf_variant_count():
 
 def sf_variant_name(v):
     return lib().fscnn_sf_variant_name(int(v)).decode()
+
+
+def sf_variant_choice(f, N, H, W, stride=(1, 1), n4=False, pool=False):
+    """fscnn_sf_variant_choice -> variant id the automatic choice takes (-1 = direct kernel)."""
+    v = ctypes.c_int(0)
+    _check(lib().fscnn_sf_variant_choice(f.handle, _i(N), _i(H), _i(W), _i(stride[0]), _i(stride[1]),
+                                         _i(1 if n4 else 0), _i(1 if pool else 0), ctypes.byref(v)),
+           "fscnn_sf_variant_choice")
+    return int(v.value)
 
 
 class SparseFilter:

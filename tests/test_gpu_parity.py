@@ -86,6 +86,21 @@ def test_filter_compress_special_values_and_empty_rows(F):
 
 
 # ------------------------------------------------------------------ A3: regrouped plan
+def test_variant_choice_names_the_kernel_that_runs(F):
+    _, w, _ = inputs.random_layer(5, 1, 24, 40, 4, 4, 3, 3, keep=0.2)
+    f = F.filter_compress(dev(w))
+    n = F.sf_variant_count()
+    for N, hw in ((32, 56), (32, 28), (32, 14), (8, 224), (1, 56), (2, 9)):
+        v = F.sf_variant_choice(f, N, hw, hw)
+        assert 1 <= v <= n
+        assert F.filter_plan_export(f, N, hw, hw, (1, 1), (1, 1))["variant"] == v
+        vp = F.sf_variant_choice(f, N, hw, hw, n4=True, pool=True)
+        assert 1 <= vp <= n and not F.sf_variant_name(vp).endswith("_n4only")
+    assert F.sf_variant_choice(f, 4, 56, 56, stride=(2, 2)) == -1      # strided: the direct kernel
+    with pytest.raises(F.FscnnError):
+        F.sf_variant_choice(f, 0, 56, 56)
+
+
 def test_plan_regroup_decodes_to_the_canonical_rows(F):
     _, w, _ = inputs.random_layer(21, 1, 37, 70, 4, 4, 3, 3, keep=0.15)
     K, C, R, S = w.shape

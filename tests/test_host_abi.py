@@ -65,6 +65,10 @@ def test_argument_checks_come_before_device_work(L):
     assert L.fscnn_conv2d_sparse_filter(ctypes.byref(junk), fake, 1, 1, 4, 4, 1, 1, 0, 0, None, 0,
                                         fake, None) == 7
     assert L.fscnn_input_info(ctypes.byref(junk), None, None, None, None, None) == 7
+    v = ctypes.c_int()
+    assert L.fscnn_sf_variant_choice(None, 1, 4, 4, 1, 1, 0, 0, ctypes.byref(v)) == 1
+    assert L.fscnn_sf_variant_choice(ctypes.byref(junk), 1, 4, 4, 1, 1, 0, 0, None) == 1
+    assert L.fscnn_sf_variant_choice(ctypes.byref(junk), 1, 4, 4, 1, 1, 0, 0, ctypes.byref(v)) == 7
 
 
 def test_no_cpu_fallback_without_a_device(L):
