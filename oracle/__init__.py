@@ -195,3 +195,33 @@ def maxpool2x2(x):
     y = np.empty((N, C, H // 2, W // 2), np.float32)
     _load().oracle_maxpool2x2(_p(x, _f32p), N, C, H, W, _p(y, _f32p))
     return y
+
+
+def sparse_transpose(rowptr, idx, val, n_rows, n_cols):
+    """Alg. 3: rows -> columns.  Returns (tptr int32[n_cols+1], tidx uint32[nnz], tval float32[nnz])."""
+    rowptr = np.ascontiguousarray(rowptr, np.int32)
+    idx = np.ascontiguousarray(idx, np.uint32)
+    val = _f32(val)
+    assert rowptr.shape == (n_rows + 1,) and idx.shape == val.shape == (int(rowptr[-1]),)
+    nnz = int(rowptr[-1])
+    tptr = np.zeros(n_cols + 1, np.int32)
+    tidx = np.zeros(nnz, np.uint32)
+    tval = np.zeros(nnz, np.float32)
+    _load().oracle_sparse_transpose(_p(rowptr, _i32p), _p(idx, _u32p), _p(val, _f32p), n_rows, n_cols,
+                                    _p(tptr, _i32p), _p(tidx, _u32p), _p(tval, _f32p))
+    return tptr, tidx, tval
+
+
+def sparse_tensor_transpose(rowptr, widx, val, W, H, C):
+    """Alg. 4: order O_whc (row c*H+h lists w) -> order O_chw (row w*H+h lists c)."""
+    rowptr = np.ascontiguousarray(rowptr, np.int32)
+    widx = np.ascontiguousarray(widx, np.uint32)
+    val = _f32(val)
+    assert rowptr.shape == (C * H + 1,) and widx.shape == val.shape == (int(rowptr[-1]),)
+    nnz = int(rowptr[-1])
+    tptr = np.zeros(W * H + 1, np.int32)
+    cidx = np.zeros(nnz, np.uint32)
+    tval = np.zeros(nnz, np.float32)
+    _load().oracle_sparse_tensor_transpose(_p(rowptr, _i32p), _p(widx, _u32p), _p(val, _f32p), W, H, C,
+                                           _p(tptr, _i32p), _p(cidx, _u32p), _p(tval, _f32p))
+    return tptr, cidx, tval

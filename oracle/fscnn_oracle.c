@@ -41,7 +41,20 @@
  * explicitly zero-padded copy of the input, impulse responses, integer-exact
  * data, 1x1 convolution == matrix product, a dense library convolution in
  * fp64, closed forms for all-ones data, linearity, numpy's nonzero() for the
- * compressed indices.  No function here is "parity unpinned".
+ * compressed indices; for the two transposes a library CSR->CSC conversion,
+ * numpy's nonzero() on the dense tensor in the target order, brute force and
+ * the involution property.  No function here is "parity unpinned".
+ *
+ *   - Sec. 4, "Sparse Matrix Transpose" (Alg. 3) and "Sparse 3-D Tensor
+ *     Transpose" (Alg. 4): reordering of the stored nodes between storage
+ *     orders.  These are algorithms, not definitions, so the oracle takes the
+ *     paper's steps in the paper's order: count the nodes per new row, turn
+ *     the counts into start positions v, walk the old rows in order placing
+ *     each node at v[index] and advancing v (Alg. 3); for a tensor, transpose
+ *     every channel's matrix first, then walk w, h, c and copy the node that
+ *     column w of matrix c has reached if its height is h (Alg. 4).  Ending
+ *     nodes (index -1) are replaced by pointer arrays throughout, as for the
+ *     filters.
  */
 #include <math.h>
 #include <stddef.h>
@@ -279,4 +292,76 @@ void oracle_maxpool2x2(const float *x, int N, int C, int H, int W, float *y)
                 if (p[W + 1] > m) m = p[W + 1];
                 y[(nc * Ho + oy) * Wo + ox] = m;
             }
+}
+
+/* Sparse matrix transpose, Alg. 3.  M has n_rows rows and n_cols columns and is
+ * stored by rows: row i holds the nodes idx[rowptr[i] .. rowptr[i+1]) = column
+ * of each stored entry, ascending, with its value.  The result stores the same
+ * entries by columns: new row j (= old column) holds the old row numbers of its
+ * entries, ascending, because the old rows are walked in order (step 5).
+ * v of the paper (start of each new row, then progress tracker) is `cursor`;
+ * without ending nodes v[j] is simply the number of nodes in columns < j. */
+void oracle_sparse_transpose(const int32_t *rowptr, const uint32_t *idx, const float *val,
+                             int n_rows, int n_cols,
+                             int32_t *tptr, uint32_t *tidx, float *tval)
+{
+    int32_t *cursor = (int32_t *)calloc((size_t)n_cols + 1, sizeof(int32_t));
+    for (int i = 0; i < n_rows; ++i)                       /* step 3: nodes per column ... */
+        for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) cursor[idx[e] + 1] += 1;
+    for (int j = 0; j < n_cols; ++j) cursor[j + 1] += cursor[j]; /* ... accumulated */
+    for (int j = 0; j <= n_cols; ++j) tptr[j] = cursor[j];
+    for (int i = 0; i < n_rows; ++i)                       /* steps 5-9 */
+        for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+            const int32_t dst = cursor[idx[e]];
+            tidx[dst] = (uint32_t)i;
+            tval[dst] = val[e];
+            cursor[idx[e]] = dst + 1;
+        }
+    free(cursor);
+}
+
+/* Sparse 3-D tensor transpose from order O_whc to order O_chw, Alg. 4.
+ * Input: C matrices stacked, matrix c stored in order O_wh, i.e. row (c*H + h)
+ * lists the w of the stored entries of channel c at height h, ascending.
+ * Output: order O_chw (channel runs innermost, then height, then width): row
+ * (w*H + h) lists the c of the stored entries at that pixel, ascending.
+ * Steps: transpose every matrix to O_hw by Alg. 3 (step 4-5: column w of matrix
+ * c then lists its heights, ascending), then for w, h, c in that nesting copy
+ * the node that column w of matrix c has reached if its height is h. */
+void oracle_sparse_tensor_transpose(const int32_t *rowptr, const uint32_t *widx, const float *val,
+                                    int W, int H, int C,
+                                    int32_t *tptr, uint32_t *cidx, float *tval)
+{
+    const long long nnz = rowptr[(long long)C * H];
+    int32_t *mptr = (int32_t *)malloc(((size_t)C * W + 1) * sizeof(int32_t));   /* per (c, w) */
+    uint32_t *hidx = (uint32_t *)malloc((size_t)(nnz > 0 ? nnz : 1) * sizeof(uint32_t));
+    float *hval = (float *)malloc((size_t)(nnz > 0 ? nnz : 1) * sizeof(float));
+    int32_t *one = (int32_t *)malloc(((size_t)W + 1) * sizeof(int32_t));
+    int32_t *local = (int32_t *)malloc(((size_t)H + 1) * sizeof(int32_t));
+    mptr[0] = 0;
+    for (int c = 0; c < C; ++c) {                           /* steps 4-5 */
+        const int32_t base = rowptr[(long long)c * H];
+        for (int h = 0; h <= H; ++h) local[h] = rowptr[(long long)c * H + h] - base;
+        oracle_sparse_transpose(local, widx + base, val + base, H, W, one, hidx + base, hval + base);
+        for (int w = 0; w < W; ++w) mptr[(long long)c * W + w + 1] = base + one[w + 1];
+    }
+    int32_t *reached = (int32_t *)malloc((size_t)C * W * sizeof(int32_t));     /* progress per (c, w) */
+    for (long long q = 0; q < (long long)C * W; ++q) reached[q] = mptr[q];
+    int32_t out = 0;
+    for (int w = 0; w < W; ++w)                             /* steps 7-13 */
+        for (int h = 0; h < H; ++h) {
+            tptr[(long long)w * H + h] = out;
+            for (int c = 0; c < C; ++c) {
+                const long long q = (long long)c * W + w;
+                const int32_t e = reached[q];
+                if (e < mptr[q + 1] && hidx[e] == (uint32_t)h) {
+                    cidx[out] = (uint32_t)c;
+                    tval[out] = hval[e];
+                    ++out;
+                    reached[q] = e + 1;
+                }
+            }
+        }
+    tptr[(long long)W * H] = out;
+    free(reached); free(local); free(one); free(hval); free(hidx); free(mptr);
 }

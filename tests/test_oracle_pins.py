@@ -289,3 +289,67 @@ def test_golden_fixture_still_reproduced():
     probe = [float(v) for v in vals["y_probe"].split()]
     pos = [int(v) for v in vals["y_probe_flat"].split()]
     assert np.array_equal(np.array(probe, np.float32), y.ravel()[pos])
+
+
+# ------------------------------------------------------------------ sparse transposes (Alg. 3, Alg. 4)
+def _csr_of(dense2d):
+    """Row-major compressed form of a 2-D array, built with numpy only (nonzero() walks row-major)."""
+    r, c = np.nonzero(dense2d)
+    ptr = np.zeros(dense2d.shape[0] + 1, np.int32)
+    np.add.at(ptr, r + 1, 1)
+    return np.cumsum(ptr).astype(np.int32), c.astype(np.uint32), dense2d[r, c].astype(np.float32)
+
+
+@pytest.mark.parametrize("shape,keep,seed", [((1, 1), 1.0, 0), ((5, 7), 0.4, 1), ((64, 33), 0.1, 2),
+                                             ((9, 200), 0.03, 3), ((40, 40), 1.0, 4), ((6, 6), 0.0, 5)])
+def test_matrix_transpose_is_the_library_csc_conversion(shape, keep, seed):
+    import scipy.sparse as sp
+    rng = np.random.default_rng(seed)
+    m = (rng.standard_normal(shape) * (rng.random(shape) < keep)).astype(np.float32)
+    ptr, idx, val = _csr_of(m)
+    tptr, tidx, tval = oracle.sparse_transpose(ptr, idx, val, *shape)
+    # pin 1: a library's CSR -> CSC conversion (CSC of M = the rows of M^T), indices sorted
+    lib = sp.csr_matrix((val, idx.astype(np.int32), ptr), shape=shape).tocsc()
+    lib.sort_indices()
+    assert np.array_equal(tptr, lib.indptr) and np.array_equal(tidx, lib.indices.astype(np.uint32))
+    assert np.array_equal(tval.view(np.uint32), lib.data.astype(np.float32).view(np.uint32))
+    # pin 2: the compressed form of the dense transpose, built with numpy only
+    p2, i2, v2 = _csr_of(np.ascontiguousarray(m.T))
+    assert np.array_equal(tptr, p2) and np.array_equal(tidx, i2) and np.array_equal(tval, v2)
+    # pin 3: transposing twice gives the matrix back
+    bptr, bidx, bval = oracle.sparse_transpose(tptr, tidx, tval, shape[1], shape[0])
+    assert np.array_equal(bptr, ptr) and np.array_equal(bidx, idx) and np.array_equal(bval, val)
+
+
+def test_matrix_transpose_keeps_stored_values_bit_for_bit():
+    # stored entries are whatever the caller stored: NaN, -0.0 and denormals travel unchanged
+    ptr = np.array([0, 2, 2, 4], np.int32)
+    idx = np.array([0, 3, 1, 3], np.uint32)
+    val = np.array([np.nan, -0.0, 1e-42, np.inf], np.float32)
+    tptr, tidx, tval = oracle.sparse_transpose(ptr, idx, val, 3, 4)
+    assert tptr.tolist() == [0, 1, 2, 2, 4] and tidx.tolist() == [0, 2, 0, 2]
+    assert tval.view(np.uint32).tolist() == val[[0, 2, 1, 3]].view(np.uint32).tolist()
+
+
+@pytest.mark.parametrize("W,H,C,keep,seed", [(1, 1, 1, 1.0, 0), (4, 3, 5, 0.5, 1), (14, 14, 40, 0.3, 2),
+                                             (7, 9, 3, 1.0, 3), (6, 5, 8, 0.0, 4), (33, 2, 17, 0.1, 5)])
+def test_tensor_transpose_whc_to_chw(W, H, C, keep, seed):
+    rng = np.random.default_rng(seed)
+    t = (rng.standard_normal((C, H, W)) * (rng.random((C, H, W)) < keep)).astype(np.float32)   # t[c, h, w]
+    # order O_whc: w runs innermost, then h, then c = the rows (c, h) of the C x H x W array
+    ptr, widx, val = _csr_of(t.reshape(C * H, W))
+    tptr, cidx, tval = oracle.sparse_tensor_transpose(ptr, widx, val, W, H, C)
+    # pin 1: order O_chw = rows (w, h) listing c: the compressed form of the array permuted to [w, h, c]
+    p2, i2, v2 = _csr_of(np.ascontiguousarray(t.transpose(2, 1, 0)).reshape(W * H, C))
+    assert np.array_equal(tptr, p2) and np.array_equal(cidx, i2) and np.array_equal(tval, v2)
+    # pin 2: brute force in Python, visiting (w, h, c) in the target order
+    want = [(w * H + h, c, t[c, h, w]) for w in range(W) for h in range(H) for c in range(C) if t[c, h, w] != 0]
+    rows = np.repeat(np.arange(W * H), np.diff(tptr))
+    assert [(int(r), int(c), v) for r, c, v in zip(rows, cidx, tval)] == want
+    # pin 3: a single Alg. 3 transpose of the (c*H + h) x w matrix has the same entries per column w
+    mptr, midx, mval = oracle.sparse_transpose(ptr, widx, val, C * H, W)
+    assert int(mptr[-1]) == int(tptr[-1])
+    for w in range(W):
+        a = sorted((int(r) % H, int(r) // H) for r in midx[mptr[w]:mptr[w + 1]])        # (h, c) pairs
+        b = sorted((h, int(c)) for h in range(H) for c in cidx[tptr[w * H + h]:tptr[w * H + h + 1]])
+        assert a == b
