@@ -150,6 +150,34 @@ def other_rows(fscnn, torch, inputs, np, dev_layers):
                                               note="same layer, dense 512x512x3x3 filter bank (values of the 95 % "
                                                    "sparse weights), compressed input")
     out["sparse_filter_density_sweep_conv4_n8"] = sweep
+    # Alg. 3 / Alg. 4: transposes of compressed operands of that layer (workspace brought by the caller:
+    # the calls allocate nothing); bytes = rowptr + index + value arrays read once and written once
+    c = inputs.config5(0.05)
+    f = fscnn.filter_compress(torch.from_numpy(c["w"]).cuda())
+    rp, ix, vl = fscnn.filter_export(f)
+    K, CRS = c["w"].shape[0], int(np.prod(c["w"].shape[1:]))
+    d_rp, d_ix, d_vl = (torch.from_numpy(rp).cuda(), torch.from_numpy(ix.view(np.int32)).cuda(),
+                        torch.from_numpy(vl).cuda())
+    ws = torch.empty(fscnn.sparse_transpose_workspace(CRS, K) // 4 + 1, dtype=torch.int32, device="cuda")
+    ms_t = time_gpu(torch, lambda: fscnn.sparse_transpose(d_rp, d_ix, d_vl, K, CRS, workspace=ws), 20)
+    out["sparse_matrix_transpose"] = dict(ms=ms_t, nnz=int(f.nnz),
+                                          gbs=(16.0 * f.nnz + 4.0 * (K + CRS + 2)) / ms_t / 1e6,
+                                          note="Alg. 3 on the 512 x 4608 matrix of the 95 % sparse filter bank; "
+                                               "incl. the binding's output allocations")
+    x0 = c["x"][0]                                                    # one image, C x H x W
+    Cc, Hh, Ww = x0.shape
+    rr, cc = np.nonzero(x0.reshape(Cc * Hh, Ww))
+    tp = np.zeros(Cc * Hh + 1, np.int64)
+    np.add.at(tp, rr + 1, 1)
+    t_rp = torch.from_numpy(np.cumsum(tp).astype(np.int32)).cuda()
+    t_ix = torch.from_numpy(cc.astype(np.int32)).cuda()
+    t_vl = torch.from_numpy(x0.reshape(Cc * Hh, Ww)[rr, cc].astype(np.float32)).cuda()
+    ws2 = torch.empty(fscnn.sparse_transpose_workspace(Ww * Hh, Cc) // 4 + 1, dtype=torch.int32, device="cuda")
+    ms_t2 = time_gpu(torch, lambda: fscnn.sparse_tensor_transpose(t_rp, t_ix, t_vl, Ww, Hh, Cc, workspace=ws2), 20)
+    out["sparse_tensor_transpose"] = dict(ms=ms_t2, nnz=int(len(rr)),
+                                          gbs=(16.0 * len(rr) + 4.0 * (Cc * Hh + Ww * Hh + 2)) / ms_t2 / 1e6,
+                                          note="Alg. 4 (O_whc -> O_chw) on one 28x28x512 activation of the same layer; "
+                                               "incl. the binding's output allocations")
     return out
 
 

@@ -212,6 +212,37 @@ fscnn_status_t fscnn_maxpool2x2(const float *x_dev, int N, int C, int H, int W, 
 fscnn_status_t fscnn_maxpool2x2_ex(const float *x_dev, int N, int C, int H, int W, float *y_dev,
                                    fscnn_layout_t layout, void *stream);
 
+/* Sparse matrix transpose (Sec. 4 "Sparse Matrix Transpose", Alg. 3).  M is n_rows x n_cols,
+ * stored by rows: rowptr_dev[n_rows+1] (starts with 0, rowptr[n_rows] = nnz), idx_dev[nnz] =
+ * column of each stored node, strictly ascending inside a row, val_dev[nnz].  The result stores
+ * the same nodes by columns: tptr_dev[n_cols+1], tidx_dev[nnz] = old row of each node, ascending
+ * inside a new row, tval_dev[nnz] (bit copies).  Ending nodes of the paper's layout are replaced
+ * by the pointer arrays.  All pointers are caller-owned device memory and must not alias;
+ * workspace_dev is scratch of at least fscnn_sparse_transpose_workspace(n_cols, n_rows) bytes,
+ * 4-byte aligned.  Allocates nothing, asynchronous on `stream`.  A node whose index is not below
+ * n_cols is dropped (never followed); rows that repeat an index give an unspecified result.
+ * ERR_UNSUPPORTED if the workspace is too small or the shape exceeds the scratch format. */
+fscnn_status_t fscnn_sparse_transpose(const int *rowptr_dev, const unsigned *idx_dev,
+                                      const float *val_dev, int n_rows, int n_cols, long long nnz,
+                                      int *tptr_dev, unsigned *tidx_dev, float *tval_dev,
+                                      void *workspace_dev, long long workspace_bytes, void *stream);
+
+/* Sparse 3-D tensor transpose from order O_whc to order O_chw (Sec. 4 "Sparse 3-D Tensor
+ * Transpose", Alg. 4).  Input: a W x H x C tensor as C stacked matrices in order O_wh: row
+ * c*H + h of rowptr_dev[C*H+1] lists in widx_dev the w of its stored nodes, strictly ascending.
+ * Output: order O_chw (channel innermost, then height, then width): row w*H + h of
+ * tptr_dev[W*H+1] lists in cidx_dev the c of its nodes, ascending; tval_dev are bit copies.
+ * Workspace: fscnn_sparse_transpose_workspace(W*H, C) bytes.  Otherwise as fscnn_sparse_transpose. */
+fscnn_status_t fscnn_sparse_tensor_transpose(const int *rowptr_dev, const unsigned *widx_dev,
+                                             const float *val_dev, int W, int H, int C,
+                                             long long nnz, int *tptr_dev, unsigned *cidx_dev,
+                                             float *tval_dev, void *workspace_dev,
+                                             long long workspace_bytes, void *stream);
+
+/* Scratch bytes the two transposes need for `new_rows` rows of the result whose nodes are
+ * ordered by an index below `index_range`; -1 if the shape is not supported.  Host-only. */
+long long fscnn_sparse_transpose_workspace(long long new_rows, long long index_range);
+
 /* Measurement helper (no counterpart in the paper): launches `work_groups` groups of 256 threads
  * that each repeat, `iters` times, the instruction mix of the convolution's hot loop on a
  * resident LDS tile -- 1 address add, 4 conflict-free ds_read_b128 (16 words per lane), 16 FMAs

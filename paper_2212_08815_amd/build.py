@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libfscnn.so")
-SOURCES = ["api.hip", "compress.hip", "conv_sf.hip", "conv_si.hip"]
+SOURCES = ["api.hip", "compress.hip", "conv_sf.hip", "conv_si.hip", "transpose.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          # packed-fp32 forms are switched off for every device function of the library

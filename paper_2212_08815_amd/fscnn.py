@@ -28,6 +28,7 @@ EXPORTS = [
     "fscnn_input_info", "fscnn_input_export", "fscnn_input_destroy", "fscnn_conv2d_sparse_input",
     "fscnn_maxpool2x2", "fscnn_conv2d_sparse_filter_ex", "fscnn_layout_convert",
     "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2", "fscnn_probe_gather_fma",
+    "fscnn_sparse_transpose", "fscnn_sparse_tensor_transpose", "fscnn_sparse_transpose_workspace",
 ]
 
 NCHW, N4 = 0, 1      # fscnn_layout_t
@@ -53,9 +54,12 @@ def lib():
         L.fscnn_sf_variant_name.restype = ctypes.c_char_p
         L.fscnn_sf_variant_name.argtypes = [ctypes.c_int]
         L.fscnn_sf_variant_count.restype = ctypes.c_int
+        L.fscnn_sparse_transpose_workspace.restype = ctypes.c_longlong
+        L.fscnn_sparse_transpose_workspace.argtypes = [ctypes.c_longlong, ctypes.c_longlong]
         for name in EXPORTS:
             fn = getattr(L, name)
-            if name not in ("fscnn_status_string", "fscnn_sf_variant_name", "fscnn_sf_variant_count"):
+            if name not in ("fscnn_status_string", "fscnn_sf_variant_name", "fscnn_sf_variant_count",
+                            "fscnn_sparse_transpose_workspace"):
                 fn.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -330,6 +334,51 @@ def maxpool2x2(x, out=None, layout=NCHW, n=None):
     _check(lib().fscnn_maxpool2x2_ex(_ptr(x), _i(N), _i(C), _i(H), _i(W), _ptr(out), _i(layout),
                                      _stream()), "fscnn_maxpool2x2_ex")
     return out
+
+
+def _dev_i32(t, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous int32 CUDA tensor" % name)
+    return t
+
+
+def sparse_transpose_workspace(new_rows, index_range):
+    return int(lib().fscnn_sparse_transpose_workspace(int(new_rows), int(index_range)))
+
+
+def _transpose(entry, rowptr, idx, val, dims, new_rows, index_range, workspace):
+    rowptr, idx, val = _dev_i32(rowptr, "rowptr"), _dev_i32(idx, "idx"), _dev_f32(val, "val")
+    nnz = idx.numel()
+    if val.numel() != nnz:
+        raise TypeError("idx and val must have one element per stored node")
+    need = sparse_transpose_workspace(new_rows, index_range)
+    if need < 0:
+        raise FscnnError(4, entry)
+    if workspace is None:
+        workspace = torch.empty((need + 3) // 4, dtype=torch.int32, device=rowptr.device)
+    tptr = torch.empty(new_rows + 1, dtype=torch.int32, device=rowptr.device)
+    tidx = torch.empty(nnz, dtype=torch.int32, device=rowptr.device)
+    tval = torch.empty(nnz, dtype=torch.float32, device=rowptr.device)
+    _check(getattr(lib(), entry)(_ptr(rowptr), _ptr(idx), _ptr(val), *[_i(d) for d in dims],
+                                 ctypes.c_longlong(nnz), _ptr(tptr), _ptr(tidx), _ptr(tval), _ptr(workspace),
+                                 ctypes.c_longlong(workspace.numel() * workspace.element_size()), _stream()), entry)
+    return tptr, tidx, tval
+
+
+def sparse_transpose(rowptr, idx, val, n_rows, n_cols, workspace=None):
+    """fscnn_sparse_transpose (Alg. 3).  rowptr/idx are int32 CUDA tensors (idx holds the u32
+    column indices), val float32; returns (tptr, tidx, tval) CUDA tensors."""
+    if rowptr.numel() != n_rows + 1:
+        raise TypeError("rowptr must have n_rows + 1 elements")
+    return _transpose("fscnn_sparse_transpose", rowptr, idx, val, (n_rows, n_cols), n_cols, n_rows, workspace)
+
+
+def sparse_tensor_transpose(rowptr, widx, val, W, H, C, workspace=None):
+    """fscnn_sparse_tensor_transpose (Alg. 4): order O_whc (row c*H+h lists w) -> order O_chw
+    (row w*H+h lists c)."""
+    if rowptr.numel() != C * H + 1:
+        raise TypeError("rowptr must have C*H + 1 elements")
+    return _transpose("fscnn_sparse_tensor_transpose", rowptr, widx, val, (W, H, C), W * H, C, workspace)
 
 
 def probe_gather_fma(iters=20000, work_groups=2048):

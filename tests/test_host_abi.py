@@ -65,6 +65,16 @@ def test_argument_checks_come_before_device_work(L):
     assert L.fscnn_conv2d_sparse_filter(ctypes.byref(junk), fake, 1, 1, 4, 4, 1, 1, 0, 0, None, 0,
                                         fake, None) == 7
     assert L.fscnn_input_info(ctypes.byref(junk), None, None, None, None, None) == 7
+    # transposes: workspace size is host arithmetic; argument checks precede any device work
+    assert L.fscnn_sparse_transpose_workspace(10, 100) == 4 * (2 * 10 * 4 + 10)
+    assert L.fscnn_sparse_transpose_workspace(0, 5) == -1 and L.fscnn_sparse_transpose_workspace(1 << 40, 1 << 40) == -1
+    ll = ctypes.c_longlong
+    assert L.fscnn_sparse_transpose(None, fake, fake, 2, 2, ll(1), fake, fake, fake, fake, ll(1 << 20), None) == 1
+    assert L.fscnn_sparse_transpose(fake, fake, fake, 0, 2, ll(1), fake, fake, fake, fake, ll(1 << 20), None) == 2
+    assert L.fscnn_sparse_transpose(fake, fake, fake, 2, 2, ll(-1), fake, fake, fake, fake, ll(1 << 20), None) == 2
+    assert L.fscnn_sparse_transpose(fake, fake, fake, 2, 2, ll(1), fake, fake, fake, fake, ll(8), None) == 4
+    assert L.fscnn_sparse_tensor_transpose(fake, fake, fake, 2, 0, 2, ll(1), fake, fake, fake, fake, ll(1 << 20), None) == 2
+    assert L.fscnn_sparse_tensor_transpose(fake, None, fake, 2, 2, 2, ll(1), fake, fake, fake, fake, ll(1 << 20), None) == 1
     v = ctypes.c_int()
     assert L.fscnn_sf_variant_choice(None, 1, 4, 4, 1, 1, 0, 0, ctypes.byref(v)) == 1
     assert L.fscnn_sf_variant_choice(ctypes.byref(junk), 1, 4, 4, 1, 1, 0, 0, None) == 1
