@@ -657,7 +657,7 @@ const Variant *variants(int *count)
     static const Variant table[] = {
         FSCNN_V4P(32, 2, 4, 4, 8, 4, 1, 3),    //  1  wide, few-channel layers: 8 waves, small chunks
         FSCNN_V4P(32, 2, 4, 4, 16, 14, 0, 2),  //  2  28x28, 56x56 with pooling: 16 waves, 4 channels each, large chunks, pipelined
-        FSCNN_V4P(16, 4, 2, 2, 16, 24, 1, 2),  //  3  14x14: 16x8 tiles, 2 channels per wave
+        FSCNN_V4P(16, 4, 2, 2, 16, 24, 4, 2),  //  3  14x14: 16x8 tiles, 2 channels per wave, 4 records per trip
         FSCNN_V4P(32, 2, 4, 2, 16, 7, 1, 2),   //  4  112x112: 2 channels per wave, two groups per CU
         FSCNN_V4P(32, 2, 2, 4, 16, 12, 1, 2),  //  5  224x224: 32x4 tiles, two groups per CU
         FSCNN_V4P(32, 2, 7, 2, 16, 9, 0, 2),   //  6  32x14 tiles: heights 28 and 56 without idle rows, pipelined
@@ -671,6 +671,7 @@ const Variant *variants(int *count)
         FSCNN_V(2, 64, 1, 4, 8, 8, 8, 2, 2),   // 14  two images per lane
         FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  // 15  as 2, two records per trip
         FSCNN_V4X(32, 2, 7, 2, 16, 9, 1, 2),   // 16  as 6, not pipelined
+        FSCNN_V4X(16, 4, 2, 2, 16, 24, 1, 2),  // 17  as 3, one record per trip
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
