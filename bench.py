@@ -72,18 +72,24 @@ def alloc_buffers(fscnn, torch, dev_layers, n, fuse_pool):
 
 
 def run_step(fscnn, x, dev_layers, n, events=None):
+    """One pass of the stack.  events: one HIP event per layer boundary (len(dev_layers) + 1) when
+    every pool is merged into its convolution, so that consecutive events bracket exactly one
+    launch; with separate pools, a (start, stop) pair per layer."""
     cur = x
+    shared = events is not None and len(events) == len(dev_layers) + 1
     for li, d in enumerate(dev_layers):
         if events is not None:
-            events[li][0].record()
+            (events[li] if shared else events[li][0]).record()
         fscnn.conv2d_sparse_filter(d["f"], cur, (1, 1), (1, 1), d["bias"], d["relu"], out=d["y"],
                                    x_layout=d["lay_in"], y_layout=d["lay_out"], n=n, pool=d["fused"])
-        if events is not None:
+        if events is not None and not shared:
             events[li][1].record()
         cur = d["y"]
         if d["pool"] and not d["fused"]:
             fscnn.maxpool2x2(cur, out=d["p"], layout=fscnn.N4, n=n)
             cur = d["p"]
+    if shared:
+        events[len(dev_layers)].record()
     return cur
 
 
@@ -259,8 +265,11 @@ def main():
         run_step(fscnn, x, dev_layers, n)
     torch.cuda.synchronize()
 
-    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for _ in dev_layers] for _ in range(args.steps)]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    if args.separate_pool:
+        events = [[(ev(), ev()) for _ in dev_layers] for _ in range(args.steps)]
+    else:
+        events = [[ev() for _ in range(len(dev_layers) + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -270,8 +279,11 @@ def main():
     ms_per_step = dt / args.steps * 1e3
 
     # per-layer kernel durations (HIP events on the launch stream, inside the timed region)
-    layer_ms = [float(np.mean([events[s][li][0].elapsed_time(events[s][li][1]) for s in range(args.steps)]))
-                for li in range(len(dev_layers))]
+    if args.separate_pool:
+        span = lambda s, li: events[s][li][0].elapsed_time(events[s][li][1])
+    else:
+        span = lambda s, li: events[s][li].elapsed_time(events[s][li + 1])
+    layer_ms = [float(np.mean([span(s, li) for s in range(args.steps)])) for li in range(len(dev_layers))]
     conv_ms = sum(layer_ms)
     # dominant kernel = the instantiation (configuration, layouts, pooled or not) with the largest
     # share of the step; its figures are means over its launches

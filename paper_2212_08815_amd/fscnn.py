@@ -124,7 +124,10 @@ class SparseFilter:
         self.nnz = nnz
 
     def __del__(self):
-        self.destroy()
+        try:
+            self.destroy()
+        except Exception:        # interpreter shutdown: the module's globals may be gone already
+            pass
 
     def destroy(self):
         if getattr(self, "_h", None):
@@ -264,7 +267,10 @@ class SparseInput:
         self.nnz = nnz
 
     def __del__(self):
-        self.destroy()
+        try:
+            self.destroy()
+        except Exception:        # interpreter shutdown: the module's globals may be gone already
+            pass
 
     def destroy(self):
         if getattr(self, "_h", None):
