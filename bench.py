@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the sparse-filter convolution hot path on one MI355X.
 
-Workload (benchmark configs[3], the one the metric is quoted on): the VGG16-shaped
+Workload (the configuration the headline metric is quoted on): the VGG16-shaped
 stack of 13 3x3 convolution layers (channels 64-64-128-128-256x3-512x3-512x3, 2x2 max-pool
 between blocks), batch N=32, 224x224x3 fp32 input ~U[0,1), 95 % random unstructured weight
 sparsity on every layer but the first (dense), bias + ReLU fused into each convolution.

@@ -737,7 +737,10 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, bool pool
     int n;
     const Variant *t = variants(&n);
     int pref[4];
-    if (N >= 4) {
+    // Fewer than four images: the one-image-per-lane forms only pay on the widest layers; from
+    // 112x112 down they launch too few work-groups, and the four-image forms with idle image
+    // slots are faster (measured on the same stack at N = 1).
+    if (N >= 4 || W <= 112) {
         if (W > 64 && C <= 8) { pref[0] = 1; pref[1] = 4; pref[2] = 3; pref[3] = 3; }
         else if (W > 128) { pref[0] = 5; pref[1] = 4; pref[2] = 2; pref[3] = 3; }
         else if (W > 64) { pref[0] = 4; pref[1] = 2; pref[2] = 3; pref[3] = 3; }
