@@ -134,7 +134,11 @@ fscnn_status_t fscnn_sf_variant_choice(const fscnn_filter_t *f, int N, int H, in
  *                  v * x[n,c,oy*stride_h - pad_h + r, ox*stride_w - pad_w + s]   (0 outside)
  *                  (+ bias_dev[k] if bias_dev != NULL) (then max(.,0) if relu != 0).
  * x_dev: N x C x H x W, y_dev: N x K x Ho x Wo (must not alias x), bias_dev: K or NULL.
- * fp32 accumulation in an order fixed by the plan (results are run-to-run identical).
+ * fp32 accumulation in an order fixed by the plan (results are run-to-run identical), except
+ * for small problems (at most 128 work-groups with the automatic configuration): there the
+ * input-channel range is split over several work-groups whose partial sums are combined with
+ * atomic adds in arrival order, so the last bits may differ between runs; an explicitly selected
+ * configuration (fscnn_conv2d_sparse_filter_v / _ex with variant > 0) never splits.
  * Asynchronous on `stream`.  FSCNN_ERR_MISMATCH if C differs from the handle's. */
 fscnn_status_t fscnn_conv2d_sparse_filter(fscnn_filter_t *f, const float *x_dev, int N, int C,
                                           int H, int W, int stride_h, int stride_w, int pad_h,

@@ -380,8 +380,10 @@ static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int 
         FSCNN_HIP(launch_conv_sf_direct(f->rowptr, f->idx, f->val, x_dev, N, C, H, W, f->K, f->R,
                                         f->S, Ho, Wo, sh, sw, ph, pw, bias_dev, relu, y_dev, st));
     } else {
+        // automatic choice only: an explicitly selected configuration runs as it is
+        const int csplit = (variant == 0 && !pool) ? sf_choose_csplit(v, N, f->K, Ho, Wo, p->NCH) : 1;
         FSCNN_HIP(launch_conv_sf_tiled(*p, x_dev, N, C, H, W, f->K, Ho, Wo, ph, pw, bias_dev, relu,
-                                       y_dev, in4, out4, pool, st));
+                                       y_dev, in4, out4, pool, csplit, st));
     }
     return FSCNN_OK;
 }

@@ -179,12 +179,21 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                      const float *__restrict__ bias, const Rec *__restrict__ recs,
                      const int *__restrict__ segptr, int N, int C, int H, int W, int K, int Ho,
                      int Wo, int ph, int pw, int relu, int NCH, int NG, int tiles_x,
-                     int tiles_per_img, int nblk)
+                     int tiles_per_img, int nblk, int csplit)
 {
     using V = typename VecT<G::BV>::T;
     extern __shared__ __align__(256) char ldsb[];
 
-    const int lid = xcd_remap(blockIdx.x, nblk);
+    // csplit > 1 (small problems): the input-channel chunks are divided among csplit
+    // work-groups per (tile, channel group); each adds its partial sums into a zeroed y and a
+    // separate pass applies bias and ReLU
+    const int lid0 = xcd_remap(blockIdx.x, nblk);
+    const int cs = lid0 % csplit;
+    const int lid = lid0 / csplit;
+    const int cper = (NCH + csplit - 1) / csplit;
+    const int ci0 = cs * cper;
+    const int ci1 = ci0 + cper < NCH ? ci0 + cper : NCH;
+    if (ci0 >= ci1) return;  // the whole work-group: nothing to add
     const int kg = lid % NG;
     const int t = (lid / NG) % tiles_per_img;
     const int n0 = (lid / (NG * tiles_per_img)) * G::IMGS;
@@ -257,7 +266,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
         for (int p = 0; p < G::P; ++p) acc[j][p] = 0.0f;
 
     // this wave's record stream, its (chunk, slot) boundaries, and the SGPR queue of records
-    const int *seg = segptr + (long long)(kg * G::WAVES + wave) * NCH * G::SLOTS;
+    const int *seg = segptr + ((long long)(kg * G::WAVES + wave) * NCH + ci0) * G::SLOTS;
     int i = seg[0];
     Rec q[G::FIFO];
 #pragma unroll
@@ -269,18 +278,18 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     // the first D chunks start loading; chunk 0 must have landed before anyone reads it
 #pragma unroll
     for (int d = 0; d < G::D; ++d)
-        if (d < NCH) fetch(d, d, 0, 1);
-    if (G::D <= NCH) wait_vmcnt<G::WAITN>(); else wait_vmcnt<0>();
+        if (ci0 + d < ci1) fetch(ci0 + d, d, 0, 1);
+    if (G::D <= ci1 - ci0) wait_vmcnt<G::WAITN>(); else wait_vmcnt<0>();
     __syncthreads();
 
     int rbuf = 0;         // ring slot of the chunk being computed
     int wbuf = G::D;      // ring slot the next load goes to (last read one chunk ago)
-    for (int ci = 0; ci < NCH; ++ci) {
+    for (int ci = ci0; ci < ci1; ++ci) {
         int nbnd[G::SLOTS];
-        const bool more = ci + G::D < NCH;  // chunk ci+D is loaded while D chunks are computed
-        if (ci + 1 < NCH) {
+        const bool more = ci + G::D < ci1;  // chunk ci+D is loaded while D chunks are computed
+        if (ci + 1 < ci1) {
 #pragma unroll
-            for (int j = 0; j < G::SLOTS; ++j) nbnd[j] = seg[(ci + 1) * G::SLOTS + j + 1];
+            for (int j = 0; j < G::SLOTS; ++j) nbnd[j] = seg[(ci + 1 - ci0) * G::SLOTS + j + 1];
         } else {
 #pragma unroll
             for (int j = 0; j < G::SLOTS; ++j) nbnd[j] = bnd[G::SLOTS - 1];
@@ -413,7 +422,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
 #pragma unroll
         for (int j = 0; j < G::SLOTS; ++j) bnd[j] = nbnd[j];
         // the next chunk's lines of this wave must be in LDS before the barrier lets anyone read
-        if (ci + G::D < NCH) wait_vmcnt<G::WAITN>(); else wait_vmcnt<0>();
+        if (ci + G::D < ci1) wait_vmcnt<G::WAITN>(); else wait_vmcnt<0>();
         __syncthreads();
     }
 
@@ -500,6 +509,12 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
             for (int v = 0; v < G::NV; ++v) {
                 const int oy = ty0 + lh * G::NV + v;
                 if (n < N && oy < Ho && ox < Wo) {
+                    if (csplit > 1) {  // partial sums of this channel range
+                        float *dst = reinterpret_cast<float *>(yk + (long long)oy * Wo + ox);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) atomicAdd(dst + b, acc[j][v * 4 + b]);
+                        continue;
+                    }
                     float r[4];
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
@@ -518,6 +533,10 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                 for (int v = 0; v < G::NV; ++v) {
                     const int oy = ty0 + lh * G::NV + v;
                     if (n < N && oy < Ho && ox < Wo) {
+                        if (csplit > 1) {
+                            atomicAdd(yk + (long long)oy * Wo + ox, acc[j][v * G::BV + b]);
+                            continue;
+                        }
                         float r = acc[j][v * G::BV + b] + bk;
                         if (relu) r = r > 0.0f ? r : 0.0f;
                         yk[(long long)oy * Wo + ox] = r;
@@ -564,13 +583,34 @@ conv_sf_direct_kernel(const int *__restrict__ rowptr, const uint32_t *__restrict
     y[(((long long)n * K + k) * Ho + oy) * Wo + ox] = acc;
 }
 
+// Helpers of the channel-split mode.
+__global__ void __launch_bounds__(256) fill_zero_kernel(float *__restrict__ y, long long n)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) y[i] = 0.0f;
+}
+
+// y = max(y + bias[k], 0): element i belongs to channel (i / (plane * inner)) % K, where inner is
+// 1 for NCHW and 4 for the batch-interleaved layout.
+__global__ void __launch_bounds__(256) bias_relu_kernel(float *__restrict__ y, const float *__restrict__ bias,
+                                                        int K, long long plane, int inner, int relu,
+                                                        long long n)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float v = y[i];
+    if (bias) v += bias[(int)((i / (plane * inner)) % K)];
+    if (relu) v = v > 0.0f ? v : 0.0f;
+    y[i] = v;
+}
+
 // ---------------------------------------------------------------- variant table
 using LaunchFn = hipError_t (*)(const SfPlan &, const float *, int, int, int, int, int, int, int,
-                                int, int, const float *, int, float *, hipStream_t);
+                                int, int, const float *, int, float *, int, hipStream_t);
 
 template <class G>
 hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K, int Ho,
-                        int Wo, int ph, int pw, const float *bias, int relu, float *y,
+                        int Wo, int ph, int pw, const float *bias, int relu, float *y, int csplit,
                         hipStream_t st)
 {
     static_assert(G::LDS_BYTES <= 160 * 1024, "tile exceeds the 160 KB LDS of a gfx950 CU");
@@ -583,11 +623,12 @@ hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, in
     const int tiles_x = (Wo + G::TW - 1) / G::TW;
     const int tiles_y = (Ho + G::TH - 1) / G::TH;
     const int nbat = (N + G::IMGS - 1) / G::IMGS;
-    const long long nblk = (long long)p.NG * tiles_x * tiles_y * nbat;
+    if (csplit < 1 || (G::POOL && csplit != 1)) return hipErrorInvalidValue;
+    const long long nblk = (long long)p.NG * tiles_x * tiles_y * nbat * csplit;
     if (nblk <= 0 || nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(conv_sf_tiled_kernel<G>, dim3((unsigned)nblk), dim3(G::NT), G::LDS_BYTES, st,
                        x, y, bias, p.recs, p.segptr, N, C, H, W, K, Ho, Wo, ph, pw, relu, p.NCH,
-                       p.NG, tiles_x, tiles_x * tiles_y, (int)nblk);
+                       p.NG, tiles_x, tiles_x * tiles_y, (int)nblk, csplit);
     return hipGetLastError();
 }
 
@@ -774,7 +815,7 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, bool pool
 
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
-                                float *y, int in4, int out4, int pool, hipStream_t st)
+                                float *y, int in4, int out4, int pool, int csplit, hipStream_t st)
 {
     int n;
     const Variant *t = variants(&n);
@@ -782,7 +823,37 @@ hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, i
     const Variant &v = t[p.variant - 1];
     LaunchFn fn = (pool ? v.pool : v.fn)[in4 ? 1 : 0][out4 ? 1 : 0];
     if (!fn) return hipErrorInvalidValue;
-    return fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, st);
+    if (csplit > 1) {
+        // partial sums are added into y: clear it first, finish with bias and ReLU afterwards
+        const long long total = (out4 ? ((long long)N + 3) / 4 * 4 : (long long)N) * K * Ho * Wo;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, y, total);
+        hipError_t e = fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, csplit, st);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(bias_relu_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, y, bias,
+                           K, (long long)Ho * Wo, out4 ? 4 : 1, relu, total);
+        return hipGetLastError();
+    }
+    return fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, 1, st);
+}
+
+// How many ways the input channels are split for a launch: small problems (deep layers at small
+// batch) leave most of the 256 CUs idle and serialise hundreds of channels in a few groups;
+// splitting the chunk range restores parallelism at the price of atomic adds into y and a
+// finishing pass, which only pays while y is small (measured: 14x14 and 28x28 at N <= 8 gain up
+// to 3.7x, 56x56 and wider lose).
+int sf_choose_csplit(int variant, int N, int K, int Ho, int Wo, int NCH)
+{
+    int n;
+    const Variant *t = variants(&n);
+    if (variant < 1 || variant > n) return 1;
+    const long long b = sf_blocks(t[variant - 1].g, N, K, Ho, Wo);
+    if (b > 128 || NCH < 4) return 1;   // with more groups the atomics cost more than they gain
+    long long s = (256 + b - 1) / b;
+    if (s > NCH / 2) s = NCH / 2;   // at least two chunks per part
+    if (s > 8) s = 8;
+    const long long outputs = (long long)N * K * Ho * Wo;
+    if (s * outputs > (4LL << 20)) s = (4LL << 20) / outputs;   // bound the atomic traffic
+    return s < 1 ? 1 : (int)s;
 }
 
 hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const float *val,

@@ -102,7 +102,9 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, bool pool
 bool sf_variant_has_layout(int variant, int in4, int out4, int pool);
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
-                                float *y, int in4, int out4, int pool, hipStream_t st);
+                                float *y, int in4, int out4, int pool, int csplit, hipStream_t st);
+// 1, or the number of parts the input-channel range is split into for a small problem
+int sf_choose_csplit(int variant, int N, int K, int Ho, int Wo, int NCH);
 hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const float *val,
                                  const float *x, int N, int C, int H, int W, int K, int R, int S,
                                  int Ho, int Wo, int sh, int sw, int ph, int pw, const float *bias,

@@ -258,6 +258,32 @@ def test_conv_n4_layouts_match_oracle(F, case):
     assert tested >= 6 + len(tiled_variants(F, n4_only=True))
 
 
+# ------------------------------------------------------------------ channel-split mode (small problems)
+@pytest.mark.parametrize("case", [(1, 200, 40, 14, 14, 0.10, True, True), (3, 130, 70, 9, 20, 0.30, True, False),
+                                  (2, 512, 33, 7, 7, 0.05, False, True), (5, 96, 64, 28, 28, 0.10, True, True)])
+def test_small_problems_split_the_channel_range(F, case):
+    """Few work-groups and many input channels: the automatic configuration splits the channel
+    chunks over several groups (atomic partial sums, then bias + ReLU in a finishing pass)."""
+    n, c, k, h, w_, keep, use_b, relu = case
+    x, w, b = inputs.random_layer(sum(case[:5]), n, c, k, h, w_, 3, 3, keep, bias=use_b)
+    csr = oracle.filter_compress(w)
+    o, a = oracle.conv2d_sparse_filter(x, csr, w.shape, (1, 1), (1, 1), b, relu, want_abs=True)
+    f = F.filter_compress(dev(w))
+    bd = dev(b) if use_b else None
+    g = host(F.conv2d_sparse_filter(f, dev(x), (1, 1), (1, 1), bd, relu))
+    assert_parity(g, o, a, row_nmax(w), "split case %r NCHW" % (case,))
+    g4 = F.conv2d_sparse_filter(f, dev(to_n4(x)), (1, 1), (1, 1), bd, relu, x_layout=F.N4, y_layout=F.N4, n=n)
+    assert_parity(from_n4(host(g4), n), o, a, row_nmax(w), "split case %r N4" % (case,))
+    # same call twice into the same buffer: the result does not accumulate across calls
+    out = F.conv2d_sparse_filter(f, dev(x), (1, 1), (1, 1), bd, relu)
+    F.conv2d_sparse_filter(f, dev(x), (1, 1), (1, 1), bd, relu, out=out)
+    assert_parity(host(out), o, a, row_nmax(w), "split case %r second call" % (case,))
+    # integer data: exact whatever the order of the partial sums
+    xi, wi, bi = inputs.random_layer(9, n, c, k, h, w_, 3, 3, keep, integer=True)
+    want = oracle.conv2d_dense(xi, wi, (1, 1), (1, 1), bi, relu)
+    assert np.array_equal(host(F.conv2d_sparse_filter(F.filter_compress(dev(wi)), dev(xi), (1, 1), (1, 1), dev(bi), relu)), want)
+
+
 # ------------------------------------------------------------------ merged convolution + max-pool
 @pytest.mark.parametrize("case", [(6, 19, 37, 23, 71, 0.30, (1, 1)), (4, 40, 9, 14, 14, 0.20, (1, 1)),
                                   (1, 8, 70, 28, 28, 0.10, (1, 1)), (5, 3, 8, 13, 66, 1.0, (0, 0))])
