@@ -155,6 +155,20 @@ def other_rows(fscnn, torch, inputs, np, dev_layers):
                                               dense_equivalent_tflops=2.0 * w.numel() * h * wd * n / ms_s / 1e9,
                                               note="same layer, dense 512x512x3x3 filter bank (values of the 95 % "
                                                    "sparse weights), compressed input")
+            dw = fscnn.dense_filter_prepare(w)
+            ms_p = time_gpu(torch, lambda: fscnn.conv2d_sparse_input_prepared(xs, dw, (1, 1), (1, 1), b, True, out=y2), 5)
+            out["conv2d_sparse_input_prepared"] = dict(
+                ms=ms_p, effective_tflops=2.0 * triples / ms_p / 1e9,
+                dense_equivalent_tflops=2.0 * w.numel() * h * wd * n / ms_p / 1e9,
+                note="same, filter bank prepared once as a K-contiguous copy (N=8: too few patches to fill the chip)")
+            x32 = torch.from_numpy(np.concatenate([c["x"]] * 4, 0)).cuda()
+            xs32 = fscnn.input_compress(x32)
+            y32 = fscnn.conv2d_sparse_input_prepared(xs32, dw, (1, 1), (1, 1), b, True)
+            ms_q = time_gpu(torch, lambda: fscnn.conv2d_sparse_input_prepared(xs32, dw, (1, 1), (1, 1), b, True, out=y32), 5)
+            out["conv2d_sparse_input_prepared_n32"] = dict(
+                ms=ms_q, effective_tflops=8.0 * triples / ms_q / 1e9,
+                dense_equivalent_tflops=8.0 * w.numel() * h * wd * n / ms_q / 1e9,
+                note="same layer with the batch repeated four times (N=32)")
     out["sparse_filter_density_sweep_conv4_n8"] = sweep
     # Alg. 3 / Alg. 4: transposes of compressed operands of that layer (workspace brought by the caller:
     # the calls allocate nothing); bytes = rowptr + index + value arrays read once and written once

@@ -216,6 +216,27 @@ fscnn_status_t fscnn_maxpool2x2(const float *x_dev, int N, int C, int H, int W, 
 fscnn_status_t fscnn_maxpool2x2_ex(const float *x_dev, int N, int C, int H, int W, float *y_dev,
                                    fscnn_layout_t layout, void *stream);
 
+/* Dense filter bank prepared for the sparse-input convolution: a K-contiguous copy
+ * wT[c][r][s][k] of w_dev (K x C x R x S, device, contiguous) that the library owns, built by one
+ * launch on `stream` (no synchronisation: use the handle on the same stream, or synchronise
+ * before using it elsewhere).  w_dev may be released once that launch has run. */
+typedef struct fscnn_dense fscnn_dense_t;
+fscnn_status_t fscnn_dense_filter_prepare(const float *w_dev, int K, int C, int R, int S, void *stream,
+                                          fscnn_dense_t **out);
+fscnn_status_t fscnn_dense_filter_destroy(fscnn_dense_t *d);
+
+/* fscnn_conv2d_sparse_input on a prepared filter bank (same result, Sec. 4 as above): lanes
+ * own adjacent output channels and read their weights as 8- or 16-byte vectors, weight chunks
+ * arrive by direct-to-LDS loads.  3x3 filters at stride 1 only (FSCNN_ERR_UNSUPPORTED otherwise:
+ * use fscnn_conv2d_sparse_input).  variant: 0 = automatic, 1..fscnn_si_variant_count() = an
+ * explicit kernel configuration (tests and benchmarks walk them).  Allocates nothing,
+ * asynchronous on `stream`; y_dev: N x K x Ho x Wo, must not alias the operands. */
+fscnn_status_t fscnn_conv2d_sparse_input_prepared(const fscnn_input_t *in, const fscnn_dense_t *d,
+                                                  int stride_h, int stride_w, int pad_h, int pad_w,
+                                                  const float *bias_dev, int relu, float *y_dev,
+                                                  int variant, void *stream);
+int fscnn_si_variant_count(void);
+
 /* Sparse matrix transpose (Sec. 4 "Sparse Matrix Transpose", Alg. 3).  M is n_rows x n_cols,
  * stored by rows: rowptr_dev[n_rows+1] (starts with 0, rowptr[n_rows] = nnz), idx_dev[nnz] =
  * column of each stored node, strictly ascending inside a row, val_dev[nnz].  The result stores

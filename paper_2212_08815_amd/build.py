@@ -39,7 +39,8 @@ def _compile(src, obj, extra):
 
 def build(force=False, extra_flags=(), verbose=True):
     os.makedirs(OBJDIR, exist_ok=True)
-    headers = [os.path.join(CSRC, "internal.h"), os.path.join(ROOT, "include", "fscnn.h"),
+    headers = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "lds_dma.h"),
+               os.path.join(ROOT, "include", "fscnn.h"),
                os.path.abspath(__file__)]
     jobs, objs = [], []
     for s in SOURCES:

@@ -52,6 +52,7 @@ fscnn_status_t have_device(int *dev)
 
 bool live(const fscnn_filter_t *f) { return f && f->magic == kFilterMagic; }
 bool live(const fscnn_input_t *i) { return i && i->magic == kInputMagic; }
+bool live(const fscnn_dense_t *d) { return d && d->magic == kDenseMagic; }
 
 void free_plan(SfPlan *p)
 {
@@ -479,9 +480,13 @@ fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e == hipSuccess) {
         in->nnz = total;
-        const size_t n = total > 0 ? (size_t)total : 1;
+        // spare entries: the sparse-input kernels fetch the next (channel, value) pair of a
+        // pixel's list ahead, up to kSiSpare positions past the one in use
+        const size_t n = (size_t)total + kSiSpare;
         e = hipMalloc(&in->cidx, sizeof(uint32_t) * n);
         if (e == hipSuccess) e = hipMalloc(&in->xval, sizeof(float) * n);
+        if (e == hipSuccess) e = hipMemsetAsync(in->cidx + total, 0, sizeof(uint32_t) * kSiSpare, st);
+        if (e == hipSuccess) e = hipMemsetAsync(in->xval + total, 0, sizeof(float) * kSiSpare, st);
     }
     if (e == hipSuccess)
         e = launch_input_fill(x_dev, N, C, H, W, in->prow, CC, NCH, in->cidx, in->xval, in->cptr, st);
@@ -559,6 +564,70 @@ fscnn_status_t fscnn_conv2d_sparse_input(const fscnn_input_t *in, const float *w
     if (s != FSCNN_OK) return s;
     FSCNN_HIP(launch_conv_si(in, w_dev, K, R, S, Ho, Wo, sh, sw, ph, pw, bias_dev, relu, y_dev,
                              (hipStream_t)stream));
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_dense_filter_prepare(const float *w_dev, int K, int C, int R, int S, void *stream,
+                                          fscnn_dense_t **out)
+{
+    if (!w_dev || !out) return FSCNN_ERR_NULL;
+    if (K <= 0 || C <= 0 || R <= 0 || S <= 0) return FSCNN_ERR_SHAPE;
+    const int Kpad = (K + 255) / 256 * 256;
+    if (!fits_int((long long)K * C * R * S) || !fits_int((long long)Kpad * C * R * S)) return FSCNN_ERR_SHAPE;
+    int dev;
+    fscnn_status_t s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    fscnn_dense_t *d = new (std::nothrow) fscnn_dense();
+    if (!d) return FSCNN_ERR_ALLOC;
+    d->magic = kDenseMagic;
+    d->device = dev;
+    d->K = K; d->C = C; d->R = R; d->S = S; d->Kpad = Kpad;
+    d->wT = nullptr;
+    hipError_t e = hipMalloc(&d->wT, sizeof(float) * (size_t)Kpad * C * R * S);
+    if (e == hipSuccess) e = launch_dense_transpose(w_dev, K, C, R * S, Kpad, d->wT, (hipStream_t)stream);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        if (d->wT) (void)hipFree(d->wT);
+        d->magic = 0;
+        delete d;
+        return e == hipErrorOutOfMemory ? FSCNN_ERR_ALLOC : FSCNN_ERR_DEVICE;
+    }
+    *out = d;
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_dense_filter_destroy(fscnn_dense_t *d)
+{
+    if (!d) return FSCNN_ERR_NULL;
+    if (!live(d)) return FSCNN_ERR_HANDLE;
+    d->magic = 0;
+    if (d->wT) (void)hipFree(d->wT);
+    delete d;
+    return FSCNN_OK;
+}
+
+int fscnn_si_variant_count(void) { return si_variant_count(); }
+
+fscnn_status_t fscnn_conv2d_sparse_input_prepared(const fscnn_input_t *in, const fscnn_dense_t *d,
+                                                  int sh, int sw, int ph, int pw,
+                                                  const float *bias_dev, int relu, float *y_dev,
+                                                  int variant, void *stream)
+{
+    if (!in || !d || !y_dev) return FSCNN_ERR_NULL;
+    if (!live(in) || !live(d)) return FSCNN_ERR_HANDLE;
+    if (d->C != in->C) return FSCNN_ERR_MISMATCH;
+    int Ho, Wo;
+    fscnn_status_t s = out_shape(in->H, in->W, d->R, d->S, sh, sw, ph, pw, &Ho, &Wo);
+    if (s != FSCNN_OK) return s;
+    if (variant < 0 || variant > si_variant_count()) return FSCNN_ERR_UNSUPPORTED;
+    // the prepared form serves 3x3 / stride 1; other geometries take fscnn_conv2d_sparse_input
+    if (d->R != 3 || d->S != 3 || sh != 1 || sw != 1) return FSCNN_ERR_UNSUPPORTED;
+    if (!fits_int((long long)in->N * d->K * Ho * Wo)) return FSCNN_ERR_UNSUPPORTED;
+    int dev;
+    s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    FSCNN_HIP(launch_conv_si_prepared(in, d, Ho, Wo, ph, pw, bias_dev, relu, y_dev, variant,
+                                      (hipStream_t)stream));
     return FSCNN_OK;
 }
 

@@ -28,6 +28,7 @@
 #include <type_traits>
 
 #include "internal.h"
+#include "lds_dma.h"
 
 namespace fscnn {
 
@@ -111,13 +112,6 @@ struct Cfg {
     static constexpr int WPE = pick_wpe();
 };
 
-// s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt is split over
-// bits 3:0 and 15:14; expcnt and lgkmcnt fields are left at "no wait")
-template <int N> __device__ inline void wait_vmcnt()
-{
-    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
-}
-
 constexpr int kInvalidOff = 0x7ffffff0;  // beyond any num_records: the buffer load returns 0
 static_assert(kPlanSpare >= 2 * 4, "a queue refill past the last record must stay inside the spare records");
 
@@ -139,30 +133,6 @@ template <> __device__ inline float vget<4>(const float4 &v, int e)
 __device__ inline void pin(const float &v) { asm volatile("" : : "v"(v)); }
 __device__ inline void pin(const float2 &v) { asm volatile("" : : "v"(v.x), "v"(v.y)); }
 __device__ inline void pin(const float4 &v) { asm volatile("" : : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
-
-typedef int int4v __attribute__((ext_vector_type(4)));
-typedef float f4v __attribute__((ext_vector_type(4)));
-
-// One buffer load that writes LDS directly (MUBUF with LDS=1): lane l deposits the dword it
-// loads at LDS byte address lds_addr + 4*l; a lane whose offset is out of the descriptor's
-// range deposits 0.0.  Written as inline assembly on purpose: the compiler does not count it
-// as an LDS store, so it puts no vmcnt wait in front of later LDS reads of the OTHER buffer.
-// The caller waits (vmcnt(0), then a barrier) before anyone reads what was loaded.
-__device__ inline void lds_dma_dwordx4(int4v rsrc, uint32_t lds_addr, int voff)
-{
-    // same, 16 bytes per lane: lane l deposits its four dwords at lds_addr + 16*l
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
-                 : "memory", "m0");
-}
-__device__ inline void lds_dma_dword(int4v rsrc, uint32_t lds_addr, int voff)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
-                 : "memory", "m0");
-}
 
 // Work-groups are dealt round-robin to the 8 XCDs; renumber them so that consecutive logical
 // ids (the channel groups of one input tile) land on the same XCD and share its L2.

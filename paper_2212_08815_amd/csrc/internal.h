@@ -13,6 +13,7 @@ namespace fscnn {
 
 constexpr uint64_t kFilterMagic = 0x4653434e4e464c54ull;  // "FSCNNFLT"
 constexpr uint64_t kInputMagic = 0x4653434e4e494e50ull;   // "FSCNNINP"
+constexpr uint64_t kDenseMagic = 0x4653434e4e44454eull;   // "FSCNNDEN"
 
 // One nonzero as the convolution kernel streams it: the byte offset of the tap
 // (c mod CC, r, s) inside the LDS input tile, and the weight (the paper's node
@@ -47,6 +48,12 @@ struct SfPlan {
 struct SiGeom {
     int CC;  // channels per chunk of the compressed activation's chunk pointers
 };
+hipError_t launch_dense_transpose(const float *w, int K, int C, int RS, int Kpad, float *wT,
+                                  hipStream_t st);
+int si_variant_count();
+hipError_t launch_conv_si_prepared(const fscnn_input *in, const fscnn_dense *d, int Ho, int Wo, int ph,
+                                   int pw, const float *bias, int relu, float *y, int variant,
+                                   hipStream_t st);
 
 }  // namespace fscnn
 
@@ -72,6 +79,15 @@ struct fscnn_input {
     uint32_t *cidx;  // device [nnz]
     float *xval;     // device [nnz]
     int *cptr;       // device [N*H*W*(NCH+1)]: first entry of pixel p with c >= j*CC
+};
+
+// Dense filter bank prepared for the sparse-input convolution: a K-contiguous copy
+// wT[c][r][s][k] (k padded to Kpad with zeros), built once.
+struct fscnn_dense {
+    uint64_t magic;
+    int device;
+    int K, C, R, S, Kpad;
+    float *wT;       // device [C*R*S*Kpad]
 };
 
 namespace fscnn {
@@ -120,7 +136,8 @@ hipError_t launch_reorder(bool tensor, const int *rowptr, const uint32_t *idx, c
                           hipStream_t st);
 
 // ---- conv_si.hip
-constexpr int kSiCC = 16;
+constexpr int kSiCC = 8;   // channels per step of the compressed activation's chunk pointers
+constexpr int kSiSpare = 8;  // entries allocated past the last (channel, value) pair (reader prefetch)
 bool si_tiled_supported(int K, int C, int R, int S, int sh, int sw);
 hipError_t launch_conv_si(const fscnn_input *in, const float *w, int K, int R, int S, int Ho, int Wo,
                           int sh, int sw, int ph, int pw, const float *bias, int relu, float *y,

@@ -29,6 +29,8 @@ EXPORTS = [
     "fscnn_maxpool2x2", "fscnn_conv2d_sparse_filter_ex", "fscnn_layout_convert",
     "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2", "fscnn_probe_gather_fma",
     "fscnn_sparse_transpose", "fscnn_sparse_tensor_transpose", "fscnn_sparse_transpose_workspace",
+    "fscnn_dense_filter_prepare", "fscnn_dense_filter_destroy", "fscnn_conv2d_sparse_input_prepared",
+    "fscnn_si_variant_count",
 ]
 
 NCHW, N4 = 0, 1      # fscnn_layout_t
@@ -328,6 +330,61 @@ def conv2d_sparse_input(s, w, stride=(1, 1), pad=(0, 0), bias=None, relu=False, 
                                            _i(stride[1]), _i(pad[0]), _i(pad[1]), _ptr(bias),
                                            _i(bool(relu)), _ptr(_dev_f32(out, "out")), _stream()),
            "fscnn_conv2d_sparse_input")
+    return out
+
+
+class DenseFilter:
+    """Owner of a fscnn_dense_t handle (K-contiguous copy of a dense filter bank)."""
+
+    def __init__(self, handle, shape):
+        self._h = handle
+        self.shape = shape
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            lib().fscnn_dense_filter_destroy(self._h)
+            self._h = None
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise RuntimeError("dense filter handle already destroyed")
+        return self._h
+
+
+def dense_filter_prepare(w):
+    """fscnn_dense_filter_prepare: dense K x C x R x S CUDA tensor -> DenseFilter."""
+    w = _dev_f32(w, "w")
+    if w.dim() != 4:
+        raise TypeError("w must be K x C x R x S")
+    K, C, R, S = w.shape
+    h = ctypes.c_void_p()
+    _check(lib().fscnn_dense_filter_prepare(_ptr(w), _i(K), _i(C), _i(R), _i(S), _stream(), ctypes.byref(h)),
+           "fscnn_dense_filter_prepare")
+    return DenseFilter(h, (K, C, R, S))
+
+
+def si_variant_count():
+    return int(lib().fscnn_si_variant_count())
+
+
+def conv2d_sparse_input_prepared(s, d, stride=(1, 1), pad=(0, 0), bias=None, relu=False, out=None, variant=0):
+    """fscnn_conv2d_sparse_input_prepared: compressed x, prepared dense filters -> y N x K x Ho x Wo."""
+    N, C, H, W = s.shape
+    K, C2, R, S = d.shape
+    Ho, Wo = conv2d_out_shape(H, W, R, S, stride, pad)
+    bias = _dev_f32(bias, "bias")
+    if out is None:
+        out = torch.empty((N, K, Ho, Wo), dtype=torch.float32, device="cuda")
+    _check(lib().fscnn_conv2d_sparse_input_prepared(s.handle, d.handle, _i(stride[0]), _i(stride[1]), _i(pad[0]),
+                                                    _i(pad[1]), _ptr(bias), _i(1 if relu else 0), _ptr(out),
+                                                    _i(variant), _stream()), "fscnn_conv2d_sparse_input_prepared")
     return out
 
 

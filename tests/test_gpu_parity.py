@@ -512,6 +512,55 @@ def test_sparse_input_integer_bit_exact(F):
     assert np.array_equal(g, o)
 
 
+@pytest.mark.parametrize("case", [
+    (2, 19, 37, 11, 23, (1, 1)),        # ragged everything: K < 128, C not a multiple of 8, odd Wo
+    (1, 40, 300, 14, 16, (1, 1)),       # three channel groups of 128, Wo a multiple of 4 (vector stores)
+    (1, 16, 64, 9, 9, (0, 0)),          # no padding
+    (3, 70, 130, 28, 28, (1, 1)),       # several tiles, several chunks
+    (1, 8, 8, 5, 5, (2, 2)),            # pad wider than the halo
+    (1, 3, 5, 1, 1, (1, 1)),            # 1x1 image
+])
+def test_conv_sparse_input_prepared_matches_oracle_all_variants(F, case):
+    n, c, k, h, w_, pad = case
+    x, w, b = inputs.random_layer(190 + c + k, n, c, k, h, w_, 3, 3, keep=0.5, x_zero_frac=0.7)
+    csx = oracle.input_compress(x)
+    o, a = oracle.conv2d_sparse_input(csx, x.shape, w, (1, 1), pad, b, True, want_abs=True)
+    s = F.input_compress(dev(x))
+    d = F.dense_filter_prepare(dev(w))
+    for v in range(0, F.si_variant_count() + 1):
+        g = host(F.conv2d_sparse_input_prepared(s, d, (1, 1), pad, dev(b), True, variant=v))
+        assert_parity(g, o, a, c * 9, "prepared sparse input %r variant %d" % (case, v))
+    g = host(F.conv2d_sparse_input_prepared(s, d, (1, 1), pad, None, False))     # no bias, no ReLU
+    o2, a2 = oracle.conv2d_sparse_input(csx, x.shape, w, (1, 1), pad, None, False, want_abs=True)
+    assert_parity(g, o2, a2, c * 9, "prepared sparse input %r plain" % (case,))
+    # integer data: bit-exact in every configuration
+    xi, wi, bi = inputs.random_layer(7, n, c, k, h, w_, 3, 3, keep=0.6, x_zero_frac=0.6, integer=True)
+    want = oracle.conv2d_dense(xi, wi, (1, 1), pad, bi, True)
+    si, di = F.input_compress(dev(xi)), F.dense_filter_prepare(dev(wi))
+    for v in range(1, F.si_variant_count() + 1):
+        assert np.array_equal(host(F.conv2d_sparse_input_prepared(si, di, (1, 1), pad, dev(bi), True, variant=v)), want)
+
+
+def test_conv_sparse_input_prepared_rejects_what_it_cannot_serve(F):
+    x, w, b = inputs.random_layer(1, 1, 6, 5, 8, 8, 3, 3, keep=0.5, x_zero_frac=0.5)
+    s = F.input_compress(dev(x))
+    d = F.dense_filter_prepare(dev(w))
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_input_prepared(s, d, (2, 2), (1, 1))                       # stride 2
+    assert e.value.status == 4
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_input_prepared(s, d, (1, 1), (1, 1), variant=99)
+    assert e.value.status == 4
+    _, w5, _ = inputs.random_layer(2, 1, 6, 5, 8, 8, 5, 5, keep=0.5)
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_input_prepared(s, F.dense_filter_prepare(dev(w5)), (1, 1), (2, 2))   # 5x5 filter
+    assert e.value.status == 4
+    _, w7, _ = inputs.random_layer(3, 1, 7, 5, 8, 8, 3, 3, keep=0.5)
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_input_prepared(s, F.dense_filter_prepare(dev(w7)), (1, 1), (1, 1))   # C differs
+    assert e.value.status == 3
+
+
 def test_config5_sparse_input_point(F):
     c = inputs.config5(0.05)
     xs = F.input_compress(dev(c["x"]))
@@ -523,6 +572,10 @@ def test_config5_sparse_input_point(F):
     flat = np.random.default_rng(6).choice(y.size, 3000, replace=False)
     o, a = oracle.conv2d_points(c["x"], c["w"], flat, c["stride"], c["pad"], c["bias"], c["relu"], want_abs=True)
     assert_parity(y.ravel()[flat], o, a, 512 * 9, "config5 sparse input")
+    d = F.dense_filter_prepare(dev(c["w"]))
+    for v in range(0, F.si_variant_count() + 1):
+        yp = host(F.conv2d_sparse_input_prepared(xs, d, c["stride"], c["pad"], dev(c["bias"]), c["relu"], variant=v))
+        assert_parity(yp.ravel()[flat], o, a, 512 * 9, "config5 prepared sparse input variant %d" % v)
 
 
 # ------------------------------------------------------------------ helper

@@ -75,6 +75,13 @@ def test_argument_checks_come_before_device_work(L):
     assert L.fscnn_sparse_transpose(fake, fake, fake, 2, 2, ll(1), fake, fake, fake, fake, ll(8), None) == 4
     assert L.fscnn_sparse_tensor_transpose(fake, fake, fake, 2, 0, 2, ll(1), fake, fake, fake, fake, ll(1 << 20), None) == 2
     assert L.fscnn_sparse_tensor_transpose(fake, None, fake, 2, 2, 2, ll(1), fake, fake, fake, fake, ll(1 << 20), None) == 1
+    assert L.fscnn_dense_filter_prepare(None, 1, 1, 3, 3, None, ctypes.byref(h)) == 1
+    assert L.fscnn_dense_filter_prepare(fake, 1, 0, 3, 3, None, ctypes.byref(h)) == 2
+    assert L.fscnn_dense_filter_destroy(None) == 1 and L.fscnn_dense_filter_destroy(ctypes.byref(junk)) == 7
+    assert L.fscnn_conv2d_sparse_input_prepared(None, fake, 1, 1, 0, 0, None, 0, fake, 0, None) == 1
+    assert L.fscnn_conv2d_sparse_input_prepared(ctypes.byref(junk), ctypes.byref(junk), 1, 1, 0, 0, None, 0,
+                                                fake, 0, None) == 7
+    assert L.fscnn_si_variant_count() >= 1
     v = ctypes.c_int()
     assert L.fscnn_sf_variant_choice(None, 1, 4, 4, 1, 1, 0, 0, ctypes.byref(v)) == 1
     assert L.fscnn_sf_variant_choice(ctypes.byref(junk), 1, 4, 4, 1, 1, 0, 0, None) == 1
