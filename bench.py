@@ -143,7 +143,7 @@ def other_rows(fscnn, torch, inputs, np, dev_layers):
             xs = fscnn.input_compress(x)
             out["input_compress"] = dict(ms=ms_c, nnz=xs.nnz, density=xs.nnz / x.numel(),
                                          gbs=(x.numel() * 4 + xs.nnz * 8) / ms_c / 1e6,
-                                         note="N=8, C=512, 28x28, ReLU(N(-0.5,1)); incl. allocation and one host sync")
+                                         note="N=8, C=512, 28x28, ReLU(N(-0.5,1)); incl. allocations and two host syncs")
             y2 = fscnn.conv2d_sparse_input(xs, w, (1, 1), (1, 1), b, True)
             ms_s = time_gpu(torch, lambda: fscnn.conv2d_sparse_input(xs, w, (1, 1), (1, 1), b, True, out=y2), 5)
             # effective work: (nonzero input, in-image tap, k) triples

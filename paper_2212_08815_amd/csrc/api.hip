@@ -95,12 +95,12 @@ fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan *
         return FSCNN_ERR_UNSUPPORTED;
     }
     int *cnt = nullptr;
-    hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)nb);
+    hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)(nb + scan_tmp_elems(nb)));
     if (e == hipSuccess) e = hipMalloc(&p->segptr, sizeof(int) * (size_t)(nb + 1));
     if (e == hipSuccess) e = hipMalloc(&p->recs, sizeof(Rec) * (size_t)(cap + kPlanSpare));
     if (e == hipSuccess)
         e = launch_plan_count(f->rowptr, f->idx, f->K, f->R * f->S, g, p->NCH, p->NG, cnt, st);
-    if (e == hipSuccess) e = launch_exclusive_scan(cnt, p->segptr, nb, st);
+    if (e == hipSuccess) e = launch_exclusive_scan(cnt, p->segptr, nb, cnt + nb, st);
     if (e == hipSuccess)
         e = launch_plan_fill(f->rowptr, f->idx, f->val, f->K, f->R, f->S, g, p->NCH, p->NG,
                              p->segptr, p->recs, st);
@@ -200,10 +200,10 @@ fscnn_status_t fscnn_filter_compress(const float *w_dev, int K, int C, int R, in
     f->rowptr = nullptr; f->idx = nullptr; f->val = nullptr;
     int *cnt = nullptr;
     int total = 0;
-    hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)K);
+    hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)(K + scan_tmp_elems(K)));
     if (e == hipSuccess) e = hipMalloc(&f->rowptr, sizeof(int) * (size_t)(K + 1));
     if (e == hipSuccess) e = launch_filter_count(w_dev, K, row, cnt, st);
-    if (e == hipSuccess) e = launch_exclusive_scan(cnt, f->rowptr, K, st);
+    if (e == hipSuccess) e = launch_exclusive_scan(cnt, f->rowptr, K, cnt + K, st);
     if (e == hipSuccess)
         e = hipMemcpyAsync(&total, f->rowptr + K, sizeof(int), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
@@ -455,7 +455,7 @@ fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int
     const long long npix = (long long)N * H * W;
     if (!fits_int(npix + 1) || !fits_int(npix * C)) return FSCNN_ERR_SHAPE;
     const int CC = kSiCC, NCH = (C + CC - 1) / CC;
-    if (!fits_int(npix * (NCH + 1))) return FSCNN_ERR_UNSUPPORTED;
+    if (!fits_int(npix * NCH + 1) || NCH > 65535) return FSCNN_ERR_UNSUPPORTED;
     int dev;
     fscnn_status_t s = have_device(&dev);
     if (s != FSCNN_OK) return s;
@@ -467,20 +467,20 @@ fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int
     in->device = dev;
     in->N = N; in->C = C; in->H = H; in->W = W;
     in->nnz = 0; in->CC = CC; in->NCH = NCH;
-    in->prow = nullptr; in->cidx = nullptr; in->xval = nullptr; in->cptr = nullptr;
+    in->cidx = nullptr; in->xval = nullptr; in->cptr = nullptr;
     int *cnt = nullptr;
     int total = 0;
-    hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)npix);
-    if (e == hipSuccess) e = hipMalloc(&in->prow, sizeof(int) * (size_t)(npix + 1));
-    if (e == hipSuccess) e = hipMalloc(&in->cptr, sizeof(int) * (size_t)(npix * (NCH + 1)));
-    if (e == hipSuccess) e = launch_input_count(x_dev, N, C, H, W, cnt, st);
-    if (e == hipSuccess) e = launch_exclusive_scan(cnt, in->prow, npix, st);
+    const long long nstep = npix * NCH;   // (pixel, channel step) pairs
+    hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)(nstep + scan_tmp_elems(nstep)));
+    if (e == hipSuccess) e = hipMalloc(&in->cptr, sizeof(int) * (size_t)(nstep + 1));
+    if (e == hipSuccess) e = launch_input_count(x_dev, N, C, H, W, CC, NCH, cnt, st);
+    if (e == hipSuccess) e = launch_exclusive_scan(cnt, in->cptr, nstep, cnt + nstep, st);
     if (e == hipSuccess)
-        e = hipMemcpyAsync(&total, in->prow + npix, sizeof(int), hipMemcpyDeviceToHost, st);
+        e = hipMemcpyAsync(&total, in->cptr + nstep, sizeof(int), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e == hipSuccess) {
         in->nnz = total;
-        // spare entries: the sparse-input kernels fetch the next (channel, value) pair of a
+        // spare entries: the sparse-input kernels fetch the next (channel, value) pairs of a
         // pixel's list ahead, up to kSiSpare positions past the one in use
         const size_t n = (size_t)total + kSiSpare;
         e = hipMalloc(&in->cidx, sizeof(uint32_t) * n);
@@ -489,12 +489,11 @@ fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int
         if (e == hipSuccess) e = hipMemsetAsync(in->xval + total, 0, sizeof(float) * kSiSpare, st);
     }
     if (e == hipSuccess)
-        e = launch_input_fill(x_dev, N, C, H, W, in->prow, CC, NCH, in->cidx, in->xval, in->cptr, st);
+        e = launch_input_fill(x_dev, N, C, H, W, CC, NCH, in->cptr, in->cidx, in->xval, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (cnt) (void)hipFree(cnt);
     if (e != hipSuccess) {
         (void)hipGetLastError();
-        if (in->prow) (void)hipFree(in->prow);
         if (in->cptr) (void)hipFree(in->cptr);
         if (in->cidx) (void)hipFree(in->cidx);
         if (in->xval) (void)hipFree(in->xval);
@@ -525,8 +524,11 @@ fscnn_status_t fscnn_input_export(const fscnn_input_t *in, int *prow_host, unsig
     if (!in || !prow_host) return FSCNN_ERR_NULL;
     if (!live(in)) return FSCNN_ERR_HANDLE;
     if (in->nnz > 0 && (!cidx_host || !val_host)) return FSCNN_ERR_NULL;
+    // the row pointers are every NCH-th chunk pointer
     const size_t npix = (size_t)in->N * in->H * in->W;
-    FSCNN_HIP(hipMemcpy(prow_host, in->prow, sizeof(int) * (npix + 1), hipMemcpyDeviceToHost));
+    FSCNN_HIP(hipMemcpy2D(prow_host, sizeof(int), in->cptr, sizeof(int) * (size_t)in->NCH, sizeof(int), npix,
+                          hipMemcpyDeviceToHost));
+    FSCNN_HIP(hipMemcpy(prow_host + npix, in->cptr + npix * (size_t)in->NCH, sizeof(int), hipMemcpyDeviceToHost));
     if (in->nnz > 0) {
         FSCNN_HIP(hipMemcpy(cidx_host, in->cidx, sizeof(uint32_t) * (size_t)in->nnz, hipMemcpyDeviceToHost));
         FSCNN_HIP(hipMemcpy(val_host, in->xval, sizeof(float) * (size_t)in->nnz, hipMemcpyDeviceToHost));
@@ -539,7 +541,6 @@ fscnn_status_t fscnn_input_destroy(fscnn_input_t *in)
     if (!in) return FSCNN_ERR_NULL;
     if (!live(in)) return FSCNN_ERR_HANDLE;
     in->magic = 0;
-    if (in->prow) (void)hipFree(in->prow);
     if (in->cptr) (void)hipFree(in->cptr);
     if (in->cidx) (void)hipFree(in->cidx);
     if (in->xval) (void)hipFree(in->xval);

@@ -87,6 +87,77 @@ __global__ void __launch_bounds__(kScanThreads) exclusive_scan_kernel(const int 
     if (threadIdx.x == kScanThreads - 1) out[n] = sums[kScanThreads - 1];
 }
 
+// ---- the same for large n, three passes over tiles of kTile elements -------------------
+// (1) every work-group adds up its tile; (2) the tile sums are scanned by the single-group
+// kernel above; (3) every work-group scans its tile starting from its tile's offset.  Tiles go
+// through LDS so that global loads and stores are contiguous while each thread scans a
+// contiguous run.
+constexpr int kTileThreads = 256, kTilePer = 16, kTile = kTileThreads * kTilePer;
+
+__global__ void __launch_bounds__(kTileThreads) scan_tile_sum_kernel(const int *__restrict__ in,
+                                                                     long long n, int *__restrict__ tsum)
+{
+    __shared__ int part[kTileThreads / 64];
+    const long long base = (long long)blockIdx.x * kTile;
+    int s = 0;
+#pragma unroll
+    for (int k = 0; k < kTilePer; ++k) {
+        const long long i = base + k * kTileThreads + threadIdx.x;
+        if (i < n) s += in[i];
+    }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
+    if (lane_id() == 0) part[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+        for (int i = 0; i < kTileThreads / 64; ++i) t += part[i];
+        tsum[blockIdx.x] = t;
+    }
+}
+
+__global__ void __launch_bounds__(kTileThreads) scan_tile_kernel(const int *__restrict__ in, long long n,
+                                                                 const int *__restrict__ toff,
+                                                                 int *__restrict__ out)
+{
+    __shared__ int tile[kTile + kTile / 32];     // padded: a thread's run of 16 starts in its own bank group
+    __shared__ int tsum[kTileThreads];
+    const long long base = (long long)blockIdx.x * kTile;
+    auto at = [](int e) { return e + e / 32; };
+#pragma unroll
+    for (int k = 0; k < kTilePer; ++k) {
+        const int e = k * kTileThreads + threadIdx.x;
+        tile[at(e)] = base + e < n ? in[base + e] : 0;
+    }
+    __syncthreads();
+    int s = 0;
+#pragma unroll
+    for (int k = 0; k < kTilePer; ++k) s += tile[at(threadIdx.x * kTilePer + k)];
+    tsum[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 1; o < kTileThreads; o <<= 1) {
+        const int v = (int)threadIdx.x >= o ? tsum[threadIdx.x - o] : 0;
+        __syncthreads();
+        tsum[threadIdx.x] += v;
+        __syncthreads();
+    }
+    int run = toff[blockIdx.x] + (threadIdx.x == 0 ? 0 : tsum[threadIdx.x - 1]);
+#pragma unroll
+    for (int k = 0; k < kTilePer; ++k) {
+        const int idx = at(threadIdx.x * kTilePer + k);
+        const int v = tile[idx];
+        tile[idx] = run;
+        run += v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kTilePer; ++k) {
+        const int e = k * kTileThreads + threadIdx.x;
+        if (base + e < n) out[base + e] = tile[at(e)];
+    }
+    // the grand total goes to out[n]
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kTileThreads - 1) out[n] = toff[gridDim.x];
+}
+
 // ---- A2: ordered pack of row k into idx/val at rowptr[k] ------------------------------
 __global__ void __launch_bounds__(kBlock) filter_pack_kernel(const float *__restrict__ w,
                                                              long long row,
@@ -194,45 +265,46 @@ __global__ void plan_fill_kernel(const int *__restrict__ rowptr, const uint32_t 
 }
 
 // ---- A7: compressed activation, rows = pixels, columns = channels ----------------------
-__global__ void __launch_bounds__(kBlock) input_count_kernel(const float *__restrict__ x, int N,
-                                                             int C, long long HW,
-                                                             int *__restrict__ cnt)
+// One thread per (pixel, step of CC channels): threads of a work-group take consecutive pixels
+// of one step, so the reads of a channel plane are contiguous.  The exclusive scan of the counts
+// in (pixel, step) order is at once the position of every step's first entry (the chunk pointers
+// the convolution kernels read) and, at step 0, the start of the pixel's row.
+__global__ void __launch_bounds__(kBlock) input_count_kernel(const float *__restrict__ x, int C,
+                                                             long long HW, long long npix, int CC,
+                                                             int NCH, int *__restrict__ cnt)
 {
     const long long p = (long long)blockIdx.x * kBlock + threadIdx.x;
-    if (p >= (long long)N * HW) return;
+    const int j = blockIdx.y;
+    if (p >= npix) return;
     const long long n = p / HW, q = p % HW;
     const float *xp = x + n * C * HW + q;
+    const int c1 = (j + 1) * CC < C ? (j + 1) * CC : C;
     int c = 0;
-    for (int ch = 0; ch < C; ++ch) c += (xp[(long long)ch * HW] != 0.0f) ? 1 : 0;
-    cnt[p] = c;
+    for (int ch = j * CC; ch < c1; ++ch) c += (xp[(long long)ch * HW] != 0.0f) ? 1 : 0;
+    cnt[p * NCH + j] = c;
 }
 
-__global__ void __launch_bounds__(kBlock) input_fill_kernel(const float *__restrict__ x, int N,
-                                                            int C, long long HW,
-                                                            const int *__restrict__ prow, int CC,
-                                                            int NCH, uint32_t *__restrict__ cidx,
-                                                            float *__restrict__ xval,
-                                                            int *__restrict__ cptr)
+__global__ void __launch_bounds__(kBlock) input_fill_kernel(const float *__restrict__ x, int C,
+                                                            long long HW, long long npix, int CC,
+                                                            int NCH, const int *__restrict__ cptr,
+                                                            uint32_t *__restrict__ cidx,
+                                                            float *__restrict__ xval)
 {
     const long long p = (long long)blockIdx.x * kBlock + threadIdx.x;
-    if (p >= (long long)N * HW) return;
+    const int j = blockIdx.y;
+    if (p >= npix) return;
     const long long n = p / HW, q = p % HW;
     const float *xp = x + n * C * HW + q;
-    int o = prow[p];
-    int *cp = cptr + p * (NCH + 1);
-    for (int j = 0; j < NCH; ++j) {
-        cp[j] = o;
-        const int c1 = (j + 1) * CC < C ? (j + 1) * CC : C;
-        for (int ch = j * CC; ch < c1; ++ch) {
-            const float v = xp[(long long)ch * HW];
-            if (v != 0.0f) {
-                cidx[o] = (uint32_t)ch;
-                xval[o] = v;
-                ++o;
-            }
+    const int c1 = (j + 1) * CC < C ? (j + 1) * CC : C;
+    int o = cptr[p * NCH + j];
+    for (int ch = j * CC; ch < c1; ++ch) {
+        const float v = xp[(long long)ch * HW];
+        if (v != 0.0f) {
+            cidx[o] = (uint32_t)ch;
+            xval[o] = v;
+            ++o;
         }
     }
-    cp[NCH] = o;
 }
 
 // ---- helper: 2x2 / stride-2 max pooling ------------------------------------------------
@@ -309,9 +381,22 @@ hipError_t launch_filter_count(const float *w, int K, long long row, int *cnt, h
     return hipGetLastError();
 }
 
-hipError_t launch_exclusive_scan(const int *in, int *out, long long n, hipStream_t st)
+long long scan_tmp_elems(long long n)
 {
-    hipLaunchKernelGGL(exclusive_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, in, out, n);
+    return n <= 4 * kTile ? 0 : 2 * ((n + kTile - 1) / kTile) + 2;
+}
+
+hipError_t launch_exclusive_scan(const int *in, int *out, long long n, int *tmp, hipStream_t st)
+{
+    if (n <= 4 * kTile) {
+        hipLaunchKernelGGL(exclusive_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, in, out, n);
+        return hipGetLastError();
+    }
+    const long long nt = (n + kTile - 1) / kTile;
+    int *tsum = tmp, *toff = tmp + nt;   // toff has nt + 1 entries
+    hipLaunchKernelGGL(scan_tile_sum_kernel, dim3((unsigned)nt), dim3(kTileThreads), 0, st, in, n, tsum);
+    hipLaunchKernelGGL(exclusive_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, tsum, toff, nt);
+    hipLaunchKernelGGL(scan_tile_kernel, dim3((unsigned)nt), dim3(kTileThreads), 0, st, in, n, toff, out);
     return hipGetLastError();
 }
 
@@ -342,20 +427,21 @@ hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float 
     return hipGetLastError();
 }
 
-hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int *cnt, hipStream_t st)
+hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int CC, int NCH, int *cnt,
+                              hipStream_t st)
 {
-    const long long HW = (long long)H * W;
-    hipLaunchKernelGGL(input_count_kernel, dim3(blocks_for(N * HW, kBlock)), dim3(kBlock), 0, st, x,
-                       N, C, HW, cnt);
+    const long long HW = (long long)H * W, npix = (long long)N * HW;
+    hipLaunchKernelGGL(input_count_kernel, dim3(blocks_for(npix, kBlock), NCH), dim3(kBlock), 0, st, x, C,
+                       HW, npix, CC, NCH, cnt);
     return hipGetLastError();
 }
 
-hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, const int *prow, int CC,
-                             int NCH, uint32_t *cidx, float *xval, int *cptr, hipStream_t st)
+hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, int CC, int NCH,
+                             const int *cptr, uint32_t *cidx, float *xval, hipStream_t st)
 {
-    const long long HW = (long long)H * W;
-    hipLaunchKernelGGL(input_fill_kernel, dim3(blocks_for(N * HW, kBlock)), dim3(kBlock), 0, st, x,
-                       N, C, HW, prow, CC, NCH, cidx, xval, cptr);
+    const long long HW = (long long)H * W, npix = (long long)N * HW;
+    hipLaunchKernelGGL(input_fill_kernel, dim3(blocks_for(npix, kBlock), NCH), dim3(kBlock), 0, st, x, C,
+                       HW, npix, CC, NCH, cptr, cidx, xval);
     return hipGetLastError();
 }
 

@@ -93,8 +93,8 @@ conv_si_tiled_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ 
                     if (ix < 0 || ix >= W) continue;
                     const long long pix = ((long long)n * H + iy) * W + ix;
                     const int last = (ci + 1) * G::CM < NCP ? (ci + 1) * G::CM : NCP;
-                    const int beg = cptr[pix * (NCP + 1) + ci * G::CM];
-                    const int end = cptr[pix * (NCP + 1) + last];
+                    const int beg = cptr[pix * NCP + ci * G::CM];
+                    const int end = cptr[pix * NCP + last];
                     for (int i = beg; i < end; ++i) {
                         const int cl = (int)cidx[i] - ci * G::CC;
                         const float v = xval[i];
@@ -216,7 +216,7 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
     const int piy = oy0 - ph + pa, pix_ = ox0 - pw + pb;
     const bool pin_img = patch_live && lane < G::NPIX && piy >= 0 && piy < H && pix_ >= 0 && pix_ < W;
     // a lane without a pixel reads the bounds of the image's first pixel and is masked afterwards
-    const int *cp = cptr + (((long long)n * H + (pin_img ? piy : 0)) * W + (pin_img ? pix_ : 0)) * (NCP + 1);
+    const int *cp = cptr + (((long long)n * H + (pin_img ? piy : 0)) * W + (pin_img ? pix_ : 0)) * NCP;
     // These loads are inline assembly like the staging loads, and for the same reason: the
     // compiler cannot count the direct-to-LDS loads, so any vector load it does know makes it
     // wait on vmcnt in the middle of the chunk for loads issued long before, and with them for
@@ -375,7 +375,7 @@ __global__ void __launch_bounds__(256) dense_transpose_kernel(const float *__res
 
 // Fallback for any stride / filter extent: one wave per output pixel, lanes along k.
 __global__ void __launch_bounds__(64)
-conv_si_direct_kernel(const int *__restrict__ prow, const uint32_t *__restrict__ cidx,
+conv_si_direct_kernel(const int *__restrict__ cptr, int NCP, const uint32_t *__restrict__ cidx,
                       const float *__restrict__ xval, const float *__restrict__ w,
                       const float *__restrict__ bias, float *__restrict__ y, int C, int H, int W,
                       int K, int R, int S, int Ho, int Wo, int sh, int sw, int ph, int pw,
@@ -398,7 +398,7 @@ conv_si_direct_kernel(const int *__restrict__ prow, const uint32_t *__restrict__
             const int ix = ox * sw - pw + s;
             if (ix < 0 || ix >= W) continue;
             const long long pix = ((long long)n * H + iy) * W + ix;
-            for (int i = prow[pix]; i < prow[pix + 1]; ++i)
+            for (int i = cptr[pix * NCP]; i < cptr[(pix + 1) * NCP]; ++i)
                 acc = __builtin_fmaf(xval[i], w[(((long long)k * C + cidx[i]) * R + r) * S + s], acc);
         }
     }
@@ -433,7 +433,7 @@ hipError_t launch_conv_si(const fscnn_input *in, const float *w, int K, int R, i
     }
     const long long nblk = (long long)NKT * Wo * Ho * in->N;
     if (nblk <= 0 || nblk > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(conv_si_direct_kernel, dim3((unsigned)nblk), dim3(64), 0, st, in->prow,
+    hipLaunchKernelGGL(conv_si_direct_kernel, dim3((unsigned)nblk), dim3(64), 0, st, in->cptr, in->NCH,
                        in->cidx, in->xval, w, bias, y, in->C, in->H, in->W, K, R, S, Ho, Wo, sh, sw,
                        ph, pw, relu, NKT);
     return hipGetLastError();

@@ -75,10 +75,10 @@ struct fscnn_input {
     int N, C, H, W;
     long long nnz;
     int CC, NCH;     // chunking of the channel axis used by cptr
-    int *prow;       // device [N*H*W + 1]
     uint32_t *cidx;  // device [nnz]
     float *xval;     // device [nnz]
-    int *cptr;       // device [N*H*W*(NCH+1)]: first entry of pixel p with c >= j*CC
+    int *cptr;       // device [N*H*W*NCH + 1]: cptr[p*NCH + j] = first entry of pixel p with
+                     // c >= j*CC; pixel p's row is [cptr[p*NCH], cptr[(p+1)*NCH])
 };
 
 // Dense filter bank prepared for the sparse-input convolution: a K-contiguous copy
@@ -94,7 +94,9 @@ namespace fscnn {
 
 // ---- compress.hip
 hipError_t launch_filter_count(const float *w, int K, long long row, int *cnt, hipStream_t st);
-hipError_t launch_exclusive_scan(const int *in, int *out, long long n, hipStream_t st);
+// out[0..n] = exclusive scan of in[0..n-1] (out[n] = total); tmp: scan_tmp_elems(n) ints of scratch
+long long scan_tmp_elems(long long n);
+hipError_t launch_exclusive_scan(const int *in, int *out, long long n, int *tmp, hipStream_t st);
 hipError_t launch_filter_pack(const float *w, int K, long long row, const int *rowptr,
                               uint32_t *idx, float *val, hipStream_t st);
 hipError_t launch_plan_count(const int *rowptr, const uint32_t *idx, int K, int RS, const SfGeom &g,
@@ -102,9 +104,10 @@ hipError_t launch_plan_count(const int *rowptr, const uint32_t *idx, int K, int 
 hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float *val, int K, int R,
                             int S, const SfGeom &g, int NCH, int NG, const int *segptr, Rec *recs,
                             hipStream_t st);
-hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int *cnt, hipStream_t st);
-hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, const int *prow, int CC,
-                             int NCH, uint32_t *cidx, float *xval, int *cptr, hipStream_t st);
+hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int CC, int NCH, int *cnt,
+                              hipStream_t st);
+hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, int CC, int NCH,
+                             const int *cptr, uint32_t *cidx, float *xval, hipStream_t st);
 hipError_t launch_maxpool2x2(const float *x, int N, int C, int H, int W, float *y, int n4,
                              hipStream_t st);
 hipError_t launch_layout_convert(const float *src, int N, int C, int H, int W, int src_n4, float *dst,

@@ -117,7 +117,7 @@ long long reorder_workspace_bytes(long long n_buckets, long long n_keys)
     const long long nw = (n_keys + 31) / 32;
     const long long words = n_buckets * nw;
     if (nw > 0x7fffffffLL || words / nw != n_buckets || words > (1LL << 33)) return -1;
-    return 4 * (2 * words + n_buckets);
+    return 4 * (2 * words + n_buckets + scan_tmp_elems(n_buckets));
 }
 
 hipError_t launch_reorder(bool tensor, const int *rowptr, const uint32_t *idx, const float *val,
@@ -143,7 +143,7 @@ hipError_t launch_reorder(bool tensor, const int *rowptr, const uint32_t *idx, c
                        n_buckets, nw, before, cnt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    e = launch_exclusive_scan(cnt, tptr, n_buckets, st);
+    e = launch_exclusive_scan(cnt, tptr, n_buckets, cnt + n_buckets, st);
     if (e != hipSuccess) return e;
     if (nnz > 0) {
         if (tensor)

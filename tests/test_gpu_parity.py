@@ -470,7 +470,9 @@ def test_config5_sparsity_sweep_sampled(F, keep):
 
 # ------------------------------------------------------------------ A7/A8: sparse-input path
 @pytest.mark.parametrize("shape,zf", [((2, 7, 5, 6), 0.7), ((1, 40, 9, 70), 0.5), ((3, 16, 1, 1), 0.0),
-                                      ((1, 33, 4, 4), 1.0)])
+                                      ((1, 33, 4, 4), 1.0),
+                                      ((2, 24, 120, 90), 0.6),      # 64 800 (pixel, step) pairs: tiled scan
+                                      ((3, 130, 57, 61), 0.9)])     # 177 327 pairs, ragged last step
 def test_input_compress_bit_exact(F, shape, zf):
     n, c, h, w_ = shape
     x, _, _ = inputs.random_layer(80 + c, n, c, 1, h, w_, 1, 1, 1.0, x_zero_frac=zf)

@@ -38,7 +38,7 @@ def same(got, want):
 
 @pytest.mark.parametrize("shape,keep,seed", [((1, 1), 1.0, 0), ((5, 7), 0.4, 1), ((64, 33), 0.1, 2), ((9, 2000), 0.03, 3),
                                              ((300, 300), 1.0, 4), ((6, 6), 0.0, 5), ((1, 4097), 0.5, 6),
-                                             ((4097, 1), 0.5, 7), ((1000, 70), 0.002, 8)])
+                                             ((4097, 1), 0.5, 7), ((1000, 70), 0.002, 8), ((7, 40000), 0.01, 9)])
 def test_matrix_transpose_matches_oracle(F, shape, keep, seed):
     rng = np.random.default_rng(seed)
     m = (rng.standard_normal(shape) * (rng.random(shape) < keep)).astype(np.float32)
@@ -73,7 +73,7 @@ def test_matrix_transpose_of_a_compressed_filter_bank_and_special_values(F):
 
 @pytest.mark.parametrize("W,H,C,keep,seed", [(1, 1, 1, 1.0, 0), (4, 3, 5, 0.5, 1), (14, 14, 40, 0.3, 2), (7, 9, 3, 1.0, 3),
                                              (6, 5, 8, 0.0, 4), (33, 2, 17, 0.1, 5), (28, 28, 512, 0.31, 6),
-                                             (56, 56, 70, 0.05, 7)])
+                                             (56, 56, 70, 0.05, 7), (150, 131, 9, 0.2, 8)])  # 19 650 new rows: tiled scan
 def test_tensor_transpose_matches_oracle(F, W, H, C, keep, seed):
     rng = np.random.default_rng(seed)
     t = (rng.standard_normal((C, H, W)) * (rng.random((C, H, W)) < keep)).astype(np.float32)
