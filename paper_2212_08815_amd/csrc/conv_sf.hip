@@ -663,6 +663,18 @@ struct Variant {
      {{&launch_tiled<FSCNN_CFGP(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>, nullptr}, \
       {nullptr, nullptr}}}
 
+// 1x1 filters, four images per lane, all four layout combinations, no pooled form
+#define FSCNN_CFG11(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, I4, O4) \
+    Cfg<4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, 1, 1, I4, O4>
+#define FSCNN_V411(LW, LHR, NV, SLOTS, WAVES, CC, U, NB)                                      \
+    {FSCNN_NAME(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB) "_r1s1",                             \
+     geom_of<FSCNN_CFG11(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>(),              \
+     {{&launch_tiled<FSCNN_CFG11(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>,        \
+       &launch_tiled<FSCNN_CFG11(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, true)>},        \
+      {&launch_tiled<FSCNN_CFG11(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, false)>,         \
+       &launch_tiled<FSCNN_CFG11(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, true)>}},        \
+     FSCNN_NOPOOL}
+
 const Variant *variants(int *count)
 {
     static const Variant table[] = {
@@ -683,6 +695,12 @@ const Variant *variants(int *count)
         FSCNN_V4X(32, 2, 4, 4, 16, 14, 2, 2),  // 15  as 2, two records per trip
         FSCNN_V4X(32, 2, 7, 2, 16, 9, 1, 2),   // 16  as 6, not pipelined
         FSCNN_V4X(16, 4, 2, 2, 16, 24, 1, 2),  // 17  as 3, one record per trip
+        // 1x1 filters: no halo, so the chunks hold more channels; a (chunk, channel) segment is
+        // still 9 times shorter than for 3x3 at the same density
+        FSCNN_V411(32, 2, 4, 4, 16, 18, 1, 2), // 18  32x8 tiles
+        FSCNN_V411(32, 2, 7, 2, 16, 10, 0, 2), // 19  32x14 tiles, pipelined
+        FSCNN_V411(16, 4, 2, 2, 16, 36, 4, 2), // 20  16x8 tiles
+        FSCNN_V411(32, 2, 4, 4, 16, 18, 2, 2), // 21  as 18, two records per trip
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
@@ -744,9 +762,16 @@ static long long sf_blocks(const SfGeom &g, int N, int K, int Ho, int Wo)
 // when one is asked for, yields to the next one.
 int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, bool pool)
 {
-    if (R != 3 || S != 3) return 0;
     int n;
     const Variant *t = variants(&n);
+    if (R == 1 && S == 1) {   // 1x1: four-image forms only, no pooled form
+        if (pool) return 0;
+        const int cand[3] = {W > 16 ? 18 : 20, 20, 19};
+        for (int i = 0; i < 3; ++i)
+            if (sf_blocks(t[cand[i] - 1].g, N, K, H, W) >= 192) return cand[i];
+        return 20;
+    }
+    if (R != 3 || S != 3) return 0;
     int pref[4];
     // Fewer than four images: the one-image-per-lane forms only pay on the widest layers; from
     // 112x112 down they launch too few work-groups, and the four-image forms with idle image

@@ -46,10 +46,12 @@ def gpu_conv(F, x, w, stride, pad, bias, relu, variant=0, filt=None):
     return host(y)
 
 
-def tiled_variants(F, n4_only=False):
-    """Kernel configurations that take NCHW tensors (or, with n4_only, those built for N4 only)."""
-    return [v for v in range(1, F.sf_variant_count() + 1)
-            if F.sf_variant_name(v).endswith("_n4only") == n4_only]
+def tiled_variants(F, n4_only=False, extent="3x3"):
+    """Kernel configurations for a filter extent that take NCHW tensors (or, with n4_only, those
+    built for N4 only).  Configurations for 1x1 filters carry "_r1s1" in their name."""
+    names = {v: F.sf_variant_name(v) for v in range(1, F.sf_variant_count() + 1)}
+    return [v for v, nm in names.items()
+            if nm.endswith("_n4only") == n4_only and ("_r1s1" in nm) == (extent == "1x1")]
 
 
 # ------------------------------------------------------------------ A1/A2: filter compression
@@ -327,7 +329,7 @@ def test_merged_conv_pool_matches_oracle_conv_then_pool(F, case):
 
 
 # ------------------------------------------------------------------ direct kernel (any stride / extent)
-@pytest.mark.parametrize("r,s,stride,pad", [(1, 1, (1, 1), (0, 0)), (3, 3, (2, 2), (1, 1)), (5, 5, (1, 1), (2, 2)),
+@pytest.mark.parametrize("r,s,stride,pad", [(1, 1, (2, 2), (0, 0)), (3, 3, (2, 2), (1, 1)), (5, 5, (1, 1), (2, 2)),
                                             (7, 7, (2, 2), (3, 3)), (2, 4, (1, 3), (0, 2)), (3, 3, (1, 2), (1, 0))])
 def test_direct_kernel_matches_oracle(F, r, s, stride, pad):
     x, w, b = inputs.random_layer(50 + r * s, 2, 10, 13, 21, 75, r, s, keep=0.3)
@@ -336,6 +338,33 @@ def test_direct_kernel_matches_oracle(F, r, s, stride, pad):
     p = F.filter_plan_export(f, 2, 21, 75, stride, pad)
     assert p["direct"]
     assert_parity(gpu_conv(F, x, w, stride, pad, b, True, filt=f), o, a, row_nmax(w), "direct")
+
+
+@pytest.mark.parametrize("case", [(2, 24, 17, 9, 70, 0.4, (0, 0)), (5, 130, 70, 28, 28, 0.05, (0, 0)),
+                                  (1, 300, 33, 14, 14, 0.2, (1, 1)), (4, 64, 256, 56, 56, 0.05, (0, 0)),
+                                  (3, 7, 5, 1, 1, 1.0, (0, 0))])
+def test_one_by_one_tiled_matches_oracle_all_variants(F, case):
+    """1x1 filters go through the tiled kernel (stride 1): every 1x1 configuration, every layout."""
+    n, c, k, h, w_, keep, pad = case
+    x, w, b = inputs.random_layer(sum(case[:5]) + 3, n, c, k, h, w_, 1, 1, keep)
+    o, a = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, (1, 1), pad, b, True, want_abs=True)
+    f = F.filter_compress(dev(w))
+    assert not F.filter_plan_export(f, n, h, w_, (1, 1), pad)["direct"]
+    xs = {F.NCHW: dev(x), F.N4: dev(to_n4(x))}
+    for v in [0] + tiled_variants(F, extent="1x1"):
+        for xl in (F.NCHW, F.N4):
+            for yl in (F.NCHW, F.N4):
+                y = F.conv2d_sparse_filter(f, xs[xl], (1, 1), pad, dev(b), True, variant=v, x_layout=xl, y_layout=yl, n=n)
+                g = host(y) if yl == F.NCHW else from_n4(host(y), n)
+                assert_parity(g, o, a, row_nmax(w), "1x1 case %r variant %d layouts %d->%d" % (case, v, xl, yl))
+    with pytest.raises(F.FscnnError) as e:            # a 3x3 configuration cannot serve a 1x1 filter
+        F.conv2d_sparse_filter(f, dev(x), (1, 1), pad, dev(b), True, variant=tiled_variants(F)[0])
+    assert e.value.status == 4
+    xi, wi, bi = inputs.random_layer(8, n, c, k, h, w_, 1, 1, keep, integer=True)
+    want = oracle.conv2d_dense(xi, wi, (1, 1), pad, bi, True)
+    fi = F.filter_compress(dev(wi))
+    for v in tiled_variants(F, extent="1x1"):
+        assert np.array_equal(host(F.conv2d_sparse_filter(fi, dev(xi), (1, 1), pad, dev(bi), True, variant=v)), want)
 
 
 def test_one_by_one_is_matrix_product_on_the_gpu(F):
