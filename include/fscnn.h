@@ -155,7 +155,8 @@ fscnn_status_t fscnn_conv2d_sparse_filter_v(fscnn_filter_t *f, const float *x_de
 /* Same operation with explicit tensor layouts for x and y (see fscnn_layout_t) and an explicit
  * kernel configuration (0 = automatic).  N4 tensors need a configuration that keeps four
  * images per lane (the automatic choice does when N >= 4); FSCNN_ERR_UNSUPPORTED otherwise,
- * for strides other than 1, or if an N4 pointer is not 16-byte aligned. */
+ * for strides other than (1,1) and, with 3x3 filters, (2,2), or if an N4 pointer is not 16-byte
+ * aligned. */
 fscnn_status_t fscnn_conv2d_sparse_filter_ex(fscnn_filter_t *f, const float *x_dev, int N,
                                              int C, int H, int W, int stride_h, int stride_w,
                                              int pad_h, int pad_w, const float *bias_dev,

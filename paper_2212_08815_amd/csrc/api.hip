@@ -81,7 +81,8 @@ fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan *
         *out = p;
         return FSCNN_OK;
     }
-    if (!sf_variant_geom(variant, f->R, f->S, &p->g)) {
+    // the configuration (validated against the call's stride by resolve_variant) fixes the stride
+    if (!sf_variant_geom(variant, f->R, f->S, 1, 1, &p->g) && !sf_variant_geom(variant, f->R, f->S, 2, 2, &p->g)) {
         delete p;
         return FSCNN_ERR_UNSUPPORTED;
     }
@@ -123,17 +124,21 @@ fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan *
 fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int sh, int sw,
                                int variant, int *resolved, bool n4 = false, bool pool = false)
 {
-    // the tiled kernel addresses up to four images' channels with 32-bit byte offsets
-    const bool tiled_ok = (sh == 1 && sw == 1) && (long long)f->C * H * W * 16 < 0x7ffffff0LL;
+    // the tiled kernel serves strides 1 and 2 (equal on both axes) and addresses up to four
+    // images' channels with 32-bit byte offsets
+    const bool tiled_ok = sh == sw && (sh == 1 || sh == 2) && (long long)f->C * H * W * 16 < 0x7ffffff0LL;
     if (variant < 0 || variant > sf_variant_count()) return FSCNN_ERR_UNSUPPORTED;
     if (variant > 0) {
         SfGeom g;
-        if (!tiled_ok || !sf_variant_geom(variant, f->R, f->S, &g)) return FSCNN_ERR_UNSUPPORTED;
+        if (!tiled_ok || !sf_variant_geom(variant, f->R, f->S, sh, sw, &g)) return FSCNN_ERR_UNSUPPORTED;
         *resolved = variant;
         return FSCNN_OK;
     }
-    // N4 tensors need four images per lane whatever the batch size
-    int v = tiled_ok ? sf_choose_variant(n4 && N < 4 ? 4 : N, f->C, f->K, H, W, f->R, f->S, pool) : 0;
+    // N4 tensors need four images per lane whatever the batch size; the choice goes by the
+    // output's extent (about the input's divided by the stride)
+    int v = tiled_ok ? sf_choose_variant(n4 && N < 4 ? 4 : N, f->C, f->K, (H + sh - 1) / sh, (W + sw - 1) / sw,
+                                         f->R, f->S, sh, pool)
+                     : 0;
     *resolved = v > 0 ? v : -1;
     return FSCNN_OK;
 }

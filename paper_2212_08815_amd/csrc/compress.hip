@@ -233,7 +233,8 @@ __global__ void plan_count_kernel(const int *__restrict__ rowptr, const uint32_t
 __global__ void plan_fill_kernel(const int *__restrict__ rowptr, const uint32_t *__restrict__ idx,
                                  const float *__restrict__ val, int K, int R, int S, int CC,
                                  int SLOTS, int WAVES, int NCH, int NG, int IN_ROWS, int PITCH,
-                                 int BV, const int *__restrict__ segptr, Rec *__restrict__ recs)
+                                 int BV, int STRIDE, const int *__restrict__ segptr,
+                                 Rec *__restrict__ recs)
 {
     const long long b = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long nb = (long long)NG * NCH * SLOTS * WAVES;
@@ -258,7 +259,9 @@ __global__ void plan_fill_kernel(const int *__restrict__ rowptr, const uint32_t 
         const int rs = (int)(f % RS);
         const int r = rs / S, s = rs % S;
         Rec rec;
-        rec.off = (uint32_t)(((c * IN_ROWS + r) * PITCH + s) * BV * 4);
+        // stride 2: tap (r, s) lies in plane (r mod 2, s mod 2) of the channel at (r/2, s/2)
+        const int plane = (r % STRIDE) * STRIDE + (s % STRIDE);
+        rec.off = (uint32_t)(((((c * STRIDE * STRIDE + plane) * IN_ROWS) + r / STRIDE) * PITCH + s / STRIDE) * BV * 4);
         rec.val = val[i];
         recs[o] = rec;
     }
@@ -422,7 +425,7 @@ hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float 
 {
     const long long nb = (long long)NG * NCH * g.KG;
     hipLaunchKernelGGL(plan_fill_kernel, dim3(blocks_for(nb, kBlock)), dim3(kBlock), 0, st, rowptr,
-                       idx, val, K, R, S, g.CC, g.SLOTS, g.WAVES, NCH, NG, g.IN_ROWS, g.PITCH, g.BV,
+                       idx, val, K, R, S, g.CC, g.SLOTS, g.WAVES, NCH, NG, g.IN_ROWS, g.PITCH, g.BV, g.STRIDE,
                        segptr, recs);
     return hipGetLastError();
 }

@@ -35,10 +35,19 @@ namespace fscnn {
 namespace {
 
 template <int BV_, int LW_, int LHR_, int NV_, int SLOTS_, int WAVES_, int CC_, int U_, int NB_, int R_, int S_,
-          bool IN4_ = false, bool OUT4_ = false, bool POOL_ = false>
+          bool IN4_ = false, bool OUT4_ = false, bool POOL_ = false, int STRIDE_ = 1>
 struct Cfg {
     static constexpr int BV = BV_, LW = LW_, LHR = LHR_, NV = NV_, SLOTS = SLOTS_, WAVES = WAVES_;
     static constexpr int CC = CC_, U = U_, NB = NB_, R = R_, S = S_;
+    // STRIDE 2 (both axes): the input tile is kept as STRIDE*STRIDE planes per channel, plane
+    // (y mod 2, x mod 2) holding every second row and column (a space-to-depth view built by the
+    // staging loads), so that adjacent lanes still read adjacent 16-byte vectors: tap (r, s) of
+    // output (oy, ox) is element (oy + r/2, ox + s/2) of plane (r mod 2, s mod 2), counted from
+    // the tile's first input row and column.
+    static constexpr int STRIDE = STRIDE_;
+    static constexpr int PL = STRIDE * STRIDE;   // planes per input channel
+    static_assert(STRIDE == 1 || STRIDE == 2, "strides 1 and 2");
+    static_assert(STRIDE == 1 || !POOL_, "no pooled form at stride 2");
     // IN4 / OUT4: the input / output tensor is stored batch-interleaved by four ("N4":
     // [N/4][C][H][W][4]) instead of NCHW; then a lane's four images are 16 contiguous bytes
     static constexpr bool IN4 = IN4_, OUT4 = OUT4_;
@@ -58,7 +67,7 @@ struct Cfg {
     static constexpr int IMGS = BV * IG;         // images per work-group
     static constexpr int P = NV * BV;            // accumulators per lane and channel
     static constexpr int TH = LHR * NV, TW = LW; // output tile
-    static constexpr int IN_ROWS = TH + R - 1;
+    static constexpr int IN_ROWS = TH + (R - 1) / STRIDE;   // rows of one plane
     // Bank conflicts of the 16-byte LDS reads, measured on gfx950 with per-lane offsets: a wave
     // whose lanes 0-31 and 32-63 each read 512 contiguous bytes is conflict-free wherever the
     // two halves lie; with four groups of 16 lanes (256 contiguous bytes each) the read is
@@ -68,7 +77,7 @@ struct Cfg {
     // until two row groups are a multiple of 256 bytes apart; for LW = 16, LHR = 2 until one is.
     static constexpr int pick_pitch()
     {
-        int p = TW + S - 1;
+        int p = TW + (S - 1) / STRIDE;
         if (LW == 16 && BV * 4 == 16 && LHR == 4)
             while ((2 * NV * p * 16) % 256 != 0) ++p;
         if (LW == 16 && BV * 4 == 16 && LHR == 2)
@@ -76,7 +85,7 @@ struct Cfg {
         return p;
     }
     static constexpr int PITCH = pick_pitch();
-    static constexpr int IG_ELEMS = CC * IN_ROWS * PITCH;  // BV-vectors per image group
+    static constexpr int IG_ELEMS = CC * PL * IN_ROWS * PITCH;  // BV-vectors per image group
     static constexpr int IG_DW = IG_ELEMS * BV;            // dwords per image group
     // one staging load fills an LDS line of 64 dwords (NCHW input) or 64 BV-vectors (N4 input)
     static constexpr int LINE_BYTES = IN4 ? 1024 : 256;
@@ -189,10 +198,11 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     for (int q = 0; q < G::NIW; ++q) {
         const int d = (wave + q * G::WAVES) * 64 + lane;  // dword (NCHW) or vector (N4) of the region
         const int e = G::IN4 ? d : d / G::BV, b = G::IN4 ? 0 : d % G::BV;
-        const int cl = e / (G::IN_ROWS * G::PITCH);
+        const int cp = e / (G::IN_ROWS * G::PITCH);   // (channel, plane) of the chunk
         const int rem = e % (G::IN_ROWS * G::PITCH);
-        const int gy = ty0 - ph + rem / G::PITCH;
-        const int gx = tx0 - pw + rem % G::PITCH;
+        const int cl = cp / G::PL, plane = cp % G::PL;
+        const int gy = ty0 * G::STRIDE - ph + (rem / G::PITCH) * G::STRIDE + plane / G::STRIDE;
+        const int gx = tx0 * G::STRIDE - pw + (rem % G::PITCH) * G::STRIDE + plane % G::STRIDE;
         const bool ok = e < G::IG_ELEMS && gy >= 0 && gy < H && gx >= 0 && gx < W;
         const int pix = cl * HW + gy * W + gx;
         goff[q] = !ok ? kInvalidOff : G::IN4 ? pix * 16 : (b * C * HW + pix) * 4;
@@ -608,6 +618,7 @@ template <class G> SfGeom geom_of()
     g.BV = G::BV; g.LW = G::LW; g.LHR = G::LHR; g.NV = G::NV; g.SLOTS = G::SLOTS;
     g.WAVES = G::WAVES; g.CC = G::CC; g.R = G::R; g.S = G::S; g.TH = G::TH; g.TW = G::TW;
     g.IMGS = G::IMGS; g.IN_ROWS = G::IN_ROWS; g.PITCH = G::PITCH; g.KG = G::KG;
+    g.STRIDE = G::STRIDE;
     g.lds_bytes = G::LDS_BYTES;
     return g;
 }
@@ -663,6 +674,17 @@ struct Variant {
      {{&launch_tiled<FSCNN_CFGP(BV, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>, nullptr}, \
       {nullptr, nullptr}}}
 
+// 3x3 filters at stride 2, four images per lane, all four layout combinations, no pooled form
+#define FSCNN_CFGS2(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, I4, O4) \
+    Cfg<4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, 3, 3, I4, O4, false, 2>
+#define FSCNN_V4S2(LW, LHR, NV, SLOTS, WAVES, CC, U, NB)                                      \
+    {FSCNN_NAME(4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB) "_st2",                              \
+     geom_of<FSCNN_CFGS2(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>(),              \
+     {{&launch_tiled<FSCNN_CFGS2(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, false)>,        \
+       &launch_tiled<FSCNN_CFGS2(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, false, true)>},        \
+      {&launch_tiled<FSCNN_CFGS2(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, false)>,         \
+       &launch_tiled<FSCNN_CFGS2(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, true, true)>}},        \
+     FSCNN_NOPOOL}
 // 1x1 filters, four images per lane, all four layout combinations, no pooled form
 #define FSCNN_CFG11(LW, LHR, NV, SLOTS, WAVES, CC, U, NB, I4, O4) \
     Cfg<4, LW, LHR, NV, SLOTS, WAVES, CC, U, NB, 1, 1, I4, O4>
@@ -701,6 +723,11 @@ const Variant *variants(int *count)
         FSCNN_V411(32, 2, 7, 2, 16, 10, 0, 2), // 19  32x14 tiles, pipelined
         FSCNN_V411(16, 4, 2, 2, 16, 36, 4, 2), // 20  16x8 tiles
         FSCNN_V411(32, 2, 4, 4, 16, 18, 2, 2), // 21  as 18, two records per trip
+        // 3x3 at stride 2: four planes per channel, so fewer channels fit a chunk
+        FSCNN_V4S2(16, 4, 2, 2, 16, 7, 1, 2),  // 22  16x8 tiles, 2 channels per wave
+        FSCNN_V4S2(32, 2, 4, 2, 16, 4, 1, 2),  // 23  32x8 tiles
+        FSCNN_V4S2(16, 4, 2, 4, 16, 7, 1, 2),  // 24  16x8 tiles, 4 channels per wave
+        FSCNN_V4S2(16, 4, 2, 2, 16, 7, 4, 2),  // 25  as 22, four records per trip
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
@@ -723,12 +750,13 @@ const char *sf_variant_name(int variant)
     return t[variant - 1].name;
 }
 
-bool sf_variant_geom(int variant, int R, int S, SfGeom *g)
+bool sf_variant_geom(int variant, int R, int S, int sh, int sw, SfGeom *g)
 {
     int n;
     const Variant *t = variants(&n);
     if (variant < 1 || variant > n) return false;
     if (t[variant - 1].g.R != R || t[variant - 1].g.S != S) return false;
+    if (t[variant - 1].g.STRIDE != sh || sh != sw) return false;
     *g = t[variant - 1].g;
     return true;
 }
@@ -760,10 +788,15 @@ static long long sf_blocks(const SfGeom &g, int N, int K, int Ho, int Wo)
 // 16x8 tiles with two channels per wave for 14x14, which keeps 256 groups of 16 waves in flight.  A configuration that
 // would launch too few work-groups to cover the 256 compute units, or that has no pooled form
 // when one is asked for, yields to the next one.
-int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, bool pool)
+int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool)
 {
     int n;
     const Variant *t = variants(&n);
+    if (stride == 2) {   // 3x3 only, four-image forms, no pooled form; H, W are the output's here
+        if (R != 3 || S != 3 || pool) return 0;
+        return sf_blocks(t[24 - 1].g, N, K, H, W) >= 192 ? 24 : 22;
+    }
+    if (stride != 1) return 0;
     if (R == 1 && S == 1) {   // 1x1: four-image forms only, no pooled form
         if (pool) return 0;
         const int cand[3] = {W > 16 ? 18 : 20, 20, 19};

@@ -30,6 +30,7 @@ struct SfGeom {
     int TH, TW, IMGS;                       // output tile and images per work-group
     int IN_ROWS, PITCH;                     // LDS rows per channel, BV-vectors per row
     int KG;                                 // output channels per work-group
+    int STRIDE;                             // stride (both axes) the instance is built for
     int lds_bytes;
 };
 
@@ -116,8 +117,9 @@ hipError_t launch_layout_convert(const float *src, int N, int C, int H, int W, i
 // ---- conv_sf.hip
 int sf_variant_count();
 const char *sf_variant_name(int variant);
-bool sf_variant_geom(int variant, int R, int S, SfGeom *g);  // false if the variant cannot serve RxS
-int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, bool pool);
+// false if the variant cannot serve RxS filters at this stride
+bool sf_variant_geom(int variant, int R, int S, int sh, int sw, SfGeom *g);
+int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool);
 bool sf_variant_has_layout(int variant, int in4, int out4, int pool);
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,

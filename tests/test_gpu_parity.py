@@ -48,10 +48,11 @@ def gpu_conv(F, x, w, stride, pad, bias, relu, variant=0, filt=None):
 
 def tiled_variants(F, n4_only=False, extent="3x3"):
     """Kernel configurations for a filter extent that take NCHW tensors (or, with n4_only, those
-    built for N4 only).  Configurations for 1x1 filters carry "_r1s1" in their name."""
+    built for N4 only).  Configurations for 1x1 filters carry "_r1s1" in their name, those for
+    3x3 filters at stride 2 "_st2" (extent "3x3s2")."""
     names = {v: F.sf_variant_name(v) for v in range(1, F.sf_variant_count() + 1)}
-    return [v for v, nm in names.items()
-            if nm.endswith("_n4only") == n4_only and ("_r1s1" in nm) == (extent == "1x1")]
+    kind = lambda nm: "1x1" if "_r1s1" in nm else "3x3s2" if "_st2" in nm else "3x3"
+    return [v for v, nm in names.items() if nm.endswith("_n4only") == n4_only and kind(nm) == extent]
 
 
 # ------------------------------------------------------------------ A1/A2: filter compression
@@ -98,7 +99,8 @@ def test_variant_choice_names_the_kernel_that_runs(F):
         assert F.filter_plan_export(f, N, hw, hw, (1, 1), (1, 1))["variant"] == v
         vp = F.sf_variant_choice(f, N, hw, hw, n4=True, pool=True)
         assert 1 <= vp <= n and not F.sf_variant_name(vp).endswith("_n4only")
-    assert F.sf_variant_choice(f, 4, 56, 56, stride=(2, 2)) == -1      # strided: the direct kernel
+    assert F.sf_variant_choice(f, 4, 56, 56, stride=(3, 3)) == -1      # stride 3: the direct kernel
+    assert "_st2" in F.sf_variant_name(F.sf_variant_choice(f, 4, 56, 56, stride=(2, 2)))
     with pytest.raises(F.FscnnError):
         F.sf_variant_choice(f, 0, 56, 56)
 
@@ -329,7 +331,7 @@ def test_merged_conv_pool_matches_oracle_conv_then_pool(F, case):
 
 
 # ------------------------------------------------------------------ direct kernel (any stride / extent)
-@pytest.mark.parametrize("r,s,stride,pad", [(1, 1, (2, 2), (0, 0)), (3, 3, (2, 2), (1, 1)), (5, 5, (1, 1), (2, 2)),
+@pytest.mark.parametrize("r,s,stride,pad", [(1, 1, (2, 2), (0, 0)), (3, 3, (3, 3), (1, 1)), (5, 5, (1, 1), (2, 2)),
                                             (7, 7, (2, 2), (3, 3)), (2, 4, (1, 3), (0, 2)), (3, 3, (1, 2), (1, 0))])
 def test_direct_kernel_matches_oracle(F, r, s, stride, pad):
     x, w, b = inputs.random_layer(50 + r * s, 2, 10, 13, 21, 75, r, s, keep=0.3)
@@ -365,6 +367,33 @@ def test_one_by_one_tiled_matches_oracle_all_variants(F, case):
     fi = F.filter_compress(dev(wi))
     for v in tiled_variants(F, extent="1x1"):
         assert np.array_equal(host(F.conv2d_sparse_filter(fi, dev(xi), (1, 1), pad, dev(bi), True, variant=v)), want)
+
+
+@pytest.mark.parametrize("case", [(2, 19, 37, 23, 71, 0.30, (1, 1)), (5, 40, 70, 28, 28, 0.10, (1, 1)),
+                                  (1, 16, 9, 14, 15, 0.5, (0, 0)), (4, 64, 128, 56, 56, 0.05, (1, 1)),
+                                  (1, 3, 5, 2, 2, 1.0, (1, 1)), (3, 8, 8, 9, 9, 0.5, (2, 2)), (1, 6, 4, 1, 1, 1.0, (1, 1))])
+def test_stride_two_tiled_matches_oracle_all_variants(F, case):
+    """3x3 filters at stride 2 go through the tiled kernel (four input planes per channel)."""
+    n, c, k, h, w_, keep, pad = case
+    x, w, b = inputs.random_layer(sum(case[:5]) + 5, n, c, k, h, w_, 3, 3, keep)
+    o, a = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, (2, 2), pad, b, True, want_abs=True)
+    f = F.filter_compress(dev(w))
+    assert not F.filter_plan_export(f, n, h, w_, (2, 2), pad)["direct"]
+    xs = {F.NCHW: dev(x), F.N4: dev(to_n4(x))}
+    for v in [0] + tiled_variants(F, extent="3x3s2"):
+        for xl in (F.NCHW, F.N4):
+            for yl in (F.NCHW, F.N4):
+                y = F.conv2d_sparse_filter(f, xs[xl], (2, 2), pad, dev(b), True, variant=v, x_layout=xl, y_layout=yl, n=n)
+                g = host(y) if yl == F.NCHW else from_n4(host(y), n)
+                assert_parity(g, o, a, row_nmax(w), "stride-2 case %r variant %d layouts %d->%d" % (case, v, xl, yl))
+    with pytest.raises(F.FscnnError) as e:            # a stride-1 configuration cannot serve stride 2
+        F.conv2d_sparse_filter(f, dev(x), (2, 2), pad, dev(b), True, variant=tiled_variants(F)[0])
+    assert e.value.status == 4
+    xi, wi, bi = inputs.random_layer(8, n, c, k, h, w_, 3, 3, keep, integer=True)
+    want = oracle.conv2d_dense(xi, wi, (2, 2), pad, bi, True)
+    fi = F.filter_compress(dev(wi))
+    for v in tiled_variants(F, extent="3x3s2"):
+        assert np.array_equal(host(F.conv2d_sparse_filter(fi, dev(xi), (2, 2), pad, dev(bi), True, variant=v)), want)
 
 
 def test_one_by_one_is_matrix_product_on_the_gpu(F):
