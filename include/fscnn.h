@@ -163,6 +163,19 @@ fscnn_status_t fscnn_conv2d_sparse_filter_ex(fscnn_filter_t *f, const float *x_d
                                              int relu, float *y_dev, fscnn_layout_t x_layout,
                                              fscnn_layout_t y_layout, int variant, void *stream);
 
+/* The same convolution followed by LeakyReLU instead of ReLU (Sec. 5 "Other layers": an
+ * element-wise activation applied to the output; the YOLO networks of Sec. 6 use this one):
+ *   y = a > 0 ? a : negative_slope * a,   a = sum (+ bias).
+ * negative_slope in [0, 1] (0 is ReLU, 1 the identity); FSCNN_ERR_SHAPE otherwise.  Batch-norm
+ * layers fold into the weights and the bias beforehand and need no kernel support.  Other
+ * arguments as fscnn_conv2d_sparse_filter_ex. */
+fscnn_status_t fscnn_conv2d_sparse_filter_leaky(fscnn_filter_t *f, const float *x_dev, int N, int C,
+                                                int H, int W, int stride_h, int stride_w,
+                                                int pad_h, int pad_w, const float *bias_dev,
+                                                float negative_slope, float *y_dev,
+                                                fscnn_layout_t x_layout, fscnn_layout_t y_layout,
+                                                int variant, void *stream);
+
 /* Merged convolution + 2x2 / stride-2 max-pooling (Alg. 7: the convolution's elements update
  * a running maximum per pooling region and only the pooled values are stored; pooled extent
  * floor(Ho/2) x floor(Wo/2) as in its step 4).  Same arguments as

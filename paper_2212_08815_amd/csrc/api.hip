@@ -404,6 +404,17 @@ fscnn_status_t fscnn_conv2d_sparse_filter_ex(fscnn_filter_t *f, const float *x_d
                           y_layout, variant, 0, stream);
 }
 
+fscnn_status_t fscnn_conv2d_sparse_filter_leaky(fscnn_filter_t *f, const float *x_dev, int N, int C,
+                                                int H, int W, int sh, int sw, int ph, int pw,
+                                                const float *bias_dev, float negative_slope,
+                                                float *y_dev, fscnn_layout_t x_layout,
+                                                fscnn_layout_t y_layout, int variant, void *stream)
+{
+    if (!(negative_slope >= 0.0f && negative_slope <= 1.0f)) return FSCNN_ERR_SHAPE;   // also rejects NaN
+    return conv_sf_common(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, act_code(negative_slope),
+                          y_dev, x_layout, y_layout, variant, 0, stream);
+}
+
 fscnn_status_t fscnn_conv2d_sparse_filter_pool2x2(fscnn_filter_t *f, const float *x_dev, int N,
                                                   int C, int H, int W, int sh, int sw, int ph,
                                                   int pw, const float *bias_dev, int relu,

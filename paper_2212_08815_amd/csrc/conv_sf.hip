@@ -431,7 +431,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                     const float o = __shfl_xor(m, 1, 64);
                     m = o > m ? o : m;
                     m += bk;
-                    if (relu) m = m > 0.0f ? m : 0.0f;
+                    m = act_apply(m, relu);
                     r[b] = m;
                 }
                 const bool ok = writer && (lx & 1) == 0 && py < Hp && px < Wp;
@@ -499,7 +499,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         r[b] = acc[j][v * 4 + b] + bk;
-                        if (relu) r[b] = r[b] > 0.0f ? r[b] : 0.0f;
+                        r[b] = act_apply(r[b], relu);
                     }
                     yk[(long long)oy * Wo + ox] = make_float4(r[0], r[1], r[2], r[3]);
                 }
@@ -518,7 +518,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                             continue;
                         }
                         float r = acc[j][v * G::BV + b] + bk;
-                        if (relu) r = r > 0.0f ? r : 0.0f;
+                        r = act_apply(r, relu);
                         yk[(long long)oy * Wo + ox] = r;
                     }
                 }
@@ -559,7 +559,7 @@ conv_sf_direct_kernel(const int *__restrict__ rowptr, const uint32_t *__restrict
             acc = __builtin_fmaf(val[i], xn[((long long)c * H + iy) * W + ix], acc);
     }
     if (bias) acc += bias[k];
-    if (relu) acc = acc > 0.0f ? acc : 0.0f;
+    acc = act_apply(acc, relu);
     y[(((long long)n * K + k) * Ho + oy) * Wo + ox] = acc;
 }
 
@@ -580,7 +580,7 @@ __global__ void __launch_bounds__(256) bias_relu_kernel(float *__restrict__ y, c
     if (i >= n) return;
     float v = y[i];
     if (bias) v += bias[(int)((i / (plane * inner)) % K)];
-    if (relu) v = v > 0.0f ? v : 0.0f;
+    v = act_apply(v, relu);
     y[i] = v;
 }
 

@@ -34,6 +34,24 @@ struct SfGeom {
     int lds_bytes;
 };
 
+// Activation code carried by the kernels' `relu` argument: 0 = none, 1 = ReLU, anything else =
+// the bit pattern of a LeakyReLU slope (y > 0 ? y : slope * y).  A slope whose bits are 0 or 1
+// (0.0f, the smallest denormal) is ReLU to rounding and is mapped to 1 by act_code().
+__host__ __device__ inline float act_apply(float r, int act)
+{
+    if (act == 0) return r;
+    if (act == 1) return r > 0.0f ? r : 0.0f;
+    union { int i; float f; } u;
+    u.i = act;
+    return r > 0.0f ? r : r * u.f;
+}
+inline int act_code(float negative_slope)
+{
+    union { int i; float f; } u;
+    u.f = negative_slope;
+    return (u.i == 0 || u.i == 1) ? 1 : u.i;
+}
+
 constexpr int kPlanSpare = 12;  // zero records appended to a plan's stream (reader prefetch)
 
 struct SfPlan {

@@ -30,7 +30,7 @@ EXPORTS = [
     "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2", "fscnn_probe_gather_fma",
     "fscnn_sparse_transpose", "fscnn_sparse_tensor_transpose", "fscnn_sparse_transpose_workspace",
     "fscnn_dense_filter_prepare", "fscnn_dense_filter_destroy", "fscnn_conv2d_sparse_input_prepared",
-    "fscnn_si_variant_count",
+    "fscnn_si_variant_count", "fscnn_conv2d_sparse_filter_leaky",
 ]
 
 NCHW, N4 = 0, 1      # fscnn_layout_t
@@ -220,10 +220,10 @@ def _logical_shape(x, layout, n):
 
 
 def conv2d_sparse_filter(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=False, out=None, variant=0,
-                         x_layout=NCHW, y_layout=NCHW, n=None, pool=False):
-    """fscnn_conv2d_sparse_filter_ex (or, with pool=True, fscnn_conv2d_sparse_filter_pool2x2):
-    x -> y (CUDA float32).  NCHW tensors are N x C x H x W; N4 tensors are
-    ceil(N/4) x C x H x W x 4 with `n` the number of real images."""
+                         x_layout=NCHW, y_layout=NCHW, n=None, pool=False, leaky=None):
+    """fscnn_conv2d_sparse_filter_ex (or, with pool=True, fscnn_conv2d_sparse_filter_pool2x2; or,
+    with leaky=slope, fscnn_conv2d_sparse_filter_leaky): x -> y (CUDA float32).  NCHW tensors are
+    N x C x H x W; N4 tensors are ceil(N/4) x C x H x W x 4 with `n` the number of real images."""
     x = _dev_f32(x, "x")
     bias = _dev_f32(bias, "bias")
     N, C, H, W = _logical_shape(x, x_layout, n)
@@ -240,6 +240,14 @@ def conv2d_sparse_filter(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=False,
             raise TypeError("out has the wrong shape")
     if bias is not None and bias.numel() != K:
         raise TypeError("bias must have K entries")
+    if leaky is not None:
+        if pool or relu:
+            raise TypeError("leaky excludes relu and pool")
+        _check(lib().fscnn_conv2d_sparse_filter_leaky(
+            f.handle, _ptr(x), _i(N), _i(C), _i(H), _i(W), _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]),
+            _ptr(bias), ctypes.c_float(float(leaky)), _ptr(out), _i(x_layout), _i(y_layout), _i(variant),
+            _stream()), "fscnn_conv2d_sparse_filter_leaky")
+        return out
     fn = lib().fscnn_conv2d_sparse_filter_pool2x2 if pool else lib().fscnn_conv2d_sparse_filter_ex
     _check(fn(f.handle, _ptr(x), _i(N), _i(C), _i(H), _i(W), _i(stride[0]), _i(stride[1]), _i(pad[0]),
               _i(pad[1]), _ptr(bias), _i(bool(relu)), _ptr(out), _i(x_layout), _i(y_layout), _i(variant),

@@ -396,6 +396,30 @@ def test_stride_two_tiled_matches_oracle_all_variants(F, case):
         assert np.array_equal(host(F.conv2d_sparse_filter(fi, dev(xi), (2, 2), pad, dev(bi), True, variant=v)), want)
 
 
+@pytest.mark.parametrize("case", [(2, 19, 37, 23, 71, 3, (1, 1), (1, 1), 0.1), (4, 64, 40, 28, 28, 3, (2, 2), (1, 1), 0.1),
+                                  (5, 130, 70, 14, 14, 1, (1, 1), (0, 0), 0.25), (1, 200, 40, 14, 14, 3, (1, 1), (1, 1), 0.1),
+                                  (2, 10, 13, 21, 30, 5, (1, 1), (2, 2), 0.01), (1, 8, 8, 9, 9, 3, (1, 1), (1, 1), 1.0)])
+def test_leaky_relu_epilogue(F, case):
+    """LeakyReLU on every kernel family: tiled 3x3, stride 2, 1x1, channel-split, direct."""
+    n, c, k, h, w_, r, stride, pad, slope = case
+    x, w, b = inputs.random_layer(sum(case[:5]) + 11, n, c, k, h, w_, r, r, 0.3)
+    o, a = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, stride, pad, b, False, want_abs=True)
+    want = np.where(o > 0, o, (o * np.float32(slope)).astype(np.float32)).astype(np.float32)
+    f = F.filter_compress(dev(w))
+    g = host(F.conv2d_sparse_filter(f, dev(x), stride, pad, dev(b), leaky=slope))
+    assert_parity(g, want, a, row_nmax(w), "leaky %r" % (case,))
+    assert (g < 0).any() or slope == 1.0 or not (o < 0).any()
+    if stride in ((1, 1), (2, 2)) and r in (1, 3):
+        g4 = F.conv2d_sparse_filter(f, dev(to_n4(x)), stride, pad, dev(b), leaky=slope, x_layout=F.N4, y_layout=F.N4, n=n)
+        assert_parity(from_n4(host(g4), n), want, a, row_nmax(w), "leaky N4 %r" % (case,))
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_filter(f, dev(x), stride, pad, dev(b), leaky=-0.5)
+    assert e.value.status == 2
+    # slope 0 is ReLU
+    gr = host(F.conv2d_sparse_filter(f, dev(x), stride, pad, dev(b), leaky=0.0))
+    assert_parity(gr, np.maximum(o, 0), a, row_nmax(w), "leaky slope 0 %r" % (case,))
+
+
 def test_one_by_one_is_matrix_product_on_the_gpu(F):
     x, w, _ = inputs.random_layer(61, 2, 24, 17, 9, 70, 1, 1, keep=0.4, integer=True, bias=False)
     g = gpu_conv(F, x, w, (1, 1), (0, 0), None, False)

@@ -59,12 +59,16 @@ def test_argument_checks_come_before_device_work(L):
     assert L.fscnn_maxpool2x2(fake, 1, 1, 1, 2, fake, None) == 2
     assert L.fscnn_conv2d_sparse_filter(None, fake, 1, 1, 4, 4, 1, 1, 0, 0, None, 0, fake, None) == 1
     assert L.fscnn_conv2d_sparse_input(None, fake, 1, 3, 3, 1, 1, 0, 0, None, 0, fake, None) == 1
+    assert L.fscnn_conv2d_sparse_filter_leaky(None, fake, 1, 1, 4, 4, 1, 1, 0, 0, None, ctypes.c_float(0.1), fake,
+                                              0, 0, 0, None) == 1
     # a block of host memory that is not a handle is rejected by its magic word
     junk = (ctypes.c_ubyte * 512)()
     assert L.fscnn_filter_info(ctypes.byref(junk), None, None, None, None, None) == 7
     assert L.fscnn_conv2d_sparse_filter(ctypes.byref(junk), fake, 1, 1, 4, 4, 1, 1, 0, 0, None, 0,
                                         fake, None) == 7
     assert L.fscnn_input_info(ctypes.byref(junk), None, None, None, None, None) == 7
+    assert L.fscnn_conv2d_sparse_filter_leaky(ctypes.byref(junk), fake, 1, 1, 4, 4, 1, 1, 0, 0, None,
+                                              ctypes.c_float(2.0), fake, 0, 0, 0, None) == 2   # slope outside [0, 1]
     # transposes: workspace size is host arithmetic; argument checks precede any device work
     assert L.fscnn_sparse_transpose_workspace(10, 100) == 4 * (2 * 10 * 4 + 10)
     assert L.fscnn_sparse_transpose_workspace(0, 5) == -1 and L.fscnn_sparse_transpose_workspace(1 << 40, 1 << 40) == -1
