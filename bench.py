@@ -198,6 +198,32 @@ def other_rows(fscnn, torch, inputs, np, dev_layers):
                                           gbs=(16.0 * len(rr) + 4.0 * (Cc * Hh + Ww * Hh + 2)) / ms_t2 / 1e6,
                                           note="Alg. 4 (O_whc -> O_chw) on one 28x28x512 activation of the same layer; "
                                                "incl. the binding's output allocations")
+    # second workload of the paper (Sec. 6): YOLO-shaped stack = Darknet-53's 52 convolutions as a
+    # chain (3x3 stride 1 and 2, 1x1, LeakyReLU 0.1), 416x416, N=32, 95 % sparse (first layer dense)
+    yn = 32
+    yx, ylayers = inputs.yolo_stack(yn, 0.05)
+    ycur = fscnn.layout_convert(torch.from_numpy(yx).cuda(), fscnn.NCHW)
+    ydev = []
+    for L in ylayers:
+        f = fscnn.filter_compress(torch.from_numpy(L["w"]).cuda())
+        k = L["w"].shape[0]
+        ho = (L["hw"] + 2 * L["pad"][0] - L["w"].shape[2]) // L["stride"][0] + 1
+        ydev.append(dict(f=f, b=torch.from_numpy(L["bias"]).cuda(), L=L, ho=ho,
+                         y=torch.empty(fscnn.n4_shape(yn, k, ho, ho), dtype=torch.float32, device="cuda")))
+
+    def ystep():
+        cur = ycur
+        for d in ydev:
+            L = d["L"]
+            fscnn.conv2d_sparse_filter(d["f"], cur, L["stride"], L["pad"], d["b"], leaky=L["leaky"], out=d["y"],
+                                       x_layout=fscnn.N4, y_layout=fscnn.N4, n=yn)
+            cur = d["y"]
+    ms_y = time_gpu(torch, ystep, 5)
+    yflop = sum(2.0 * d["f"].nnz * d["ho"] * d["ho"] * yn for d in ydev)
+    out["yolo_shaped_stack"] = dict(ms=ms_y, effective_tflops=yflop / ms_y / 1e9, effective_gflop=yflop / 1e9,
+                                    nnz_total=int(sum(d["f"].nnz for d in ydev)),
+                                    note="52 convolution layers of Darknet-53 as a chain, N=32, 416x416, weight "
+                                         "density 0.05 (first layer dense), bias + LeakyReLU(0.1) fused, N4 between layers")
     return out
 
 

@@ -87,6 +87,43 @@ def config4(n=32, **kw):
     return vgg16_stack(4, n, 0.05, **kw)
 
 
+def yolo_layers():
+    """Convolution layers of the Darknet-53 feature extractor (the backbone of YOLOv3, as its
+    public description lists them): (C_in, C_out, filter extent, stride), in order.  Residual
+    additions, up-sampling and detection heads are not convolutions and are left out: the
+    stack below is the plain chain of these 52 layers."""
+    layers = [(3, 32, 3, 1)]
+    c = 32
+    for blocks in (1, 2, 8, 8, 4):
+        layers.append((c, 2 * c, 3, 2))          # down-sampling convolution
+        c *= 2
+        for _ in range(blocks):
+            layers.append((c, c // 2, 1, 1))     # bottleneck
+            layers.append((c // 2, c, 3, 1))
+    return layers
+
+
+def yolo_stack(n, keep, hw0=416, width_div=1, config_id=6):
+    """YOLO-shaped stack (the paper's second workload, Sec. 6): Darknet-53's 52 convolution
+    layers as a chain, 3x3 (stride 1 and 2, pad 1) and 1x1 filters, LeakyReLU(0.1), first layer
+    dense, the others Bernoulli(keep); batch-norm is taken as folded into weights and bias.
+    `hw0` is the input size, `width_div` divides every channel count (small test cases)."""
+    x = _rng(config_id, 0, "x").random((n, 3, hw0, hw0), dtype=np.float32)
+    out = []
+    hw = hw0
+    for li, (c, k, r, st) in enumerate(yolo_layers()):
+        c = c if li == 0 else max(c // width_div, 1)
+        k = max(k // width_div, 1)
+        d = 1.0 if li == 0 else keep
+        # LeakyReLU(0.1) keeps about half of the variance: same scale rule as the VGG16 stack
+        std = float(np.sqrt(2.0 / (r * r * c * d)))
+        w = masked_normal(_rng(config_id, li, "w"), _rng(config_id, li, "mask"), (k, c, r, r), std, d)
+        b = _rng(config_id, li, "bias").standard_normal(k, dtype=np.float32) * np.float32(0.01)
+        out.append(dict(w=w, bias=b, leaky=0.1, stride=(st, st), pad=(r // 2, r // 2), hw=hw))
+        hw = (hw + 2 * (r // 2) - r) // st + 1
+    return x, out
+
+
 CONFIG5_KEEP = (0.5, 0.2, 0.1, 0.05, 0.01)
 
 

@@ -550,6 +550,39 @@ def test_config5_sparsity_sweep_sampled(F, keep):
     assert_parity(y.ravel()[flat], o, a, row_nmax(c["w"]), "config5 keep %g" % keep)
 
 
+# ------------------------------------------------------------------ YOLO-shaped stack (second workload)
+def test_yolo_shaped_stack_chain(F):
+    """Darknet-53's 52 convolutions as a chain (3x3 stride 1 and 2, 1x1, LeakyReLU 0.1), reduced
+    width and image size: every layer against the oracle on the GPU's own previous output, N4
+    tensors handed from layer to layer, and the whole chain against the oracle's own chain."""
+    n = 4
+    x, layers = inputs.yolo_stack(n, 0.3, hw0=64, width_div=8)
+    assert len(layers) == 52 and layers[-1]["hw"] == 2
+    cur = dev(to_n4(x))
+    cur_host = x
+    oc = x                                        # the oracle's own chain
+    kinds = set()
+    for li, L in enumerate(layers):
+        w, b, st, pad = L["w"], L["bias"], L["stride"], L["pad"]
+        f = F.filter_compress(dev(w))
+        p = F.filter_plan_export(f, n, L["hw"], L["hw"], st, pad)
+        assert not p["direct"]
+        kinds.add(F.sf_variant_name(p["variant"]).split("_")[-1] if "_" in F.sf_variant_name(p["variant"]) else "")
+        y = F.conv2d_sparse_filter(f, cur, st, pad, dev(b), leaky=L["leaky"], x_layout=F.N4, y_layout=F.N4, n=n)
+        g = from_n4(host(y), n)
+        csr = oracle.filter_compress(w)
+        o, a = oracle.conv2d_sparse_filter(cur_host, csr, w.shape, st, pad, b, False, want_abs=True)
+        want = np.where(o > 0, o, o * np.float32(L["leaky"])).astype(np.float32)
+        assert_parity(g, want, a, row_nmax(w), "yolo layer %d" % li)
+        o2 = oracle.conv2d_sparse_filter(oc, csr, w.shape, st, pad, b, False)
+        oc = np.where(o2 > 0, o2, o2 * np.float32(L["leaky"])).astype(np.float32)
+        cur, cur_host = y, g
+    assert {"st2", "r1s1"} <= kinds               # stride-2 and 1x1 configurations were exercised
+    # 52 layers of fp32 rounding against the double-accumulating oracle chain
+    scale = float(np.sqrt(np.mean(oc.astype(np.float64) ** 2)))
+    assert np.max(np.abs(cur_host - oc)) <= 2e-4 * max(scale, 1e-30)
+
+
 # ------------------------------------------------------------------ A7/A8: sparse-input path
 @pytest.mark.parametrize("shape,zf", [((2, 7, 5, 6), 0.7), ((1, 40, 9, 70), 0.5), ((3, 16, 1, 1), 0.0),
                                       ((1, 33, 4, 4), 1.0),
