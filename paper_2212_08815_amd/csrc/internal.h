@@ -39,11 +39,15 @@ struct SfGeom {
 // (0.0f, the smallest denormal) is ReLU to rounding and is mapped to 1 by act_code().
 __host__ __device__ inline float act_apply(float r, int act)
 {
-    if (act == 0) return r;
-    if (act == 1) return r > 0.0f ? r : 0.0f;
-    union { int i; float f; } u;
-    u.i = act;
-    return r > 0.0f ? r : r * u.f;
+    // none / ReLU first (the common cases: one compare-and-select); the LeakyReLU fix-up sits
+    // behind a branch on the wave-uniform code so that the other two do not pay for it
+    float y = act == 1 ? (r > 0.0f ? r : 0.0f) : r;
+    if (__builtin_expect((act & ~1) != 0, 0)) {
+        union { int i; float f; } u;
+        u.i = act;
+        y = r > 0.0f ? r : r * u.f;
+    }
+    return y;
 }
 inline int act_code(float negative_slope)
 {
