@@ -139,7 +139,6 @@ template <> __device__ inline float vget<4>(const float4 &v, int e)
 
 // Keeps a loaded value live at this point of the program: the optimiser would otherwise sink
 // an LDS read into the conditional block that consumes it and serialise the reads of a trip.
-__device__ inline void pin(const float &v) { asm volatile("" : : "v"(v)); }
 __device__ inline void pin(const float2 &v) { asm volatile("" : : "v"(v.x), "v"(v.y)); }
 __device__ inline void pin(const float4 &v) { asm volatile("" : : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
 
