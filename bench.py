@@ -161,6 +161,14 @@ def other_rows(fscnn, torch, inputs, np, dev_layers):
                 ms=ms_p, effective_tflops=2.0 * triples / ms_p / 1e9,
                 dense_equivalent_tflops=2.0 * w.numel() * h * wd * n / ms_p / 1e9,
                 note="same, filter bank prepared once as a K-contiguous copy (N=8: too few patches to fill the chip)")
+            # sparse output emission: the sparse-filter convolution of this layer returning its
+            # ReLU output compressed (a dense temporary inside), next to the convolution alone
+            ms_e = time_gpu(torch, lambda: fscnn.conv2d_sparse_filter_emit(f, x, (1, 1), (1, 1), b, True), 5)
+            es = fscnn.conv2d_sparse_filter_emit(f, x, (1, 1), (1, 1), b, True)
+            out["conv2d_sparse_filter_emit"] = dict(
+                ms=ms_e, conv_alone_ms=ms, nnz_out=es.nnz, density_out=es.nnz / y.numel(),
+                note="same layer at 95 % weight sparsity: convolution + ReLU + compression of the result "
+                     "in one call; incl. allocations and two host syncs")
             x32 = torch.from_numpy(np.concatenate([c["x"]] * 4, 0)).cuda()
             xs32 = fscnn.input_compress(x32)
             y32 = fscnn.conv2d_sparse_input_prepared(xs32, dw, (1, 1), (1, 1), b, True)

@@ -210,6 +210,23 @@ fscnn_status_t fscnn_input_export(const fscnn_input_t *in, int *prow_host, unsig
                                   float *val_host);
 fscnn_status_t fscnn_input_destroy(fscnn_input_t *in);
 
+/* Sparse-filter convolution with sparse output (Sec. 4, the paragraph on sparse outputs of
+ * "Sparse Tensor Convolution": only the non-zero results are kept as nodes, so that the
+ * next layer can take a sparse input).  Computes y exactly as fscnn_conv2d_sparse_filter
+ * does (NCHW x, bias nullable, relu as there) and returns it compressed as
+ * fscnn_input_compress would: a handle of shape N x K x Ho x Wo whose pixel rows list the
+ * (channel, value) pairs with y != 0.0f.  y_dev may be NULL; if it is not, the dense
+ * N x K x Ho x Wo result is left there as well (caller-owned, must not alias x).  With
+ * y_dev NULL the call allocates and frees a dense temporary of that size.  Allocates the
+ * handle's buffers and synchronises `stream` (the number of stored values sizes them);
+ * *out is owned by the caller (fscnn_input_destroy).  Errors as the two calls it stands
+ * for; on error *out is untouched. */
+fscnn_status_t fscnn_conv2d_sparse_filter_emit(fscnn_filter_t *f, const float *x_dev, int N, int C,
+                                               int H, int W, int stride_h, int stride_w,
+                                               int pad_h, int pad_w, const float *bias_dev,
+                                               int relu, float *y_dev, void *stream,
+                                               fscnn_input_t **out);
+
 /* Sparse-input convolution (Sec. 4, last paragraph of "Sparse Tensor Convolution": the
  * loops of Alg. 1 with a sparse T_I and dense filters; zero activations are skipped):
  * same result definition as above with w_dev the dense K x C x R x S bank.  The output is

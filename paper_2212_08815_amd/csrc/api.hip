@@ -463,10 +463,11 @@ fscnn_status_t fscnn_conv2d_sparse_filter(fscnn_filter_t *f, const float *x_dev,
                                         0, stream);
 }
 
-fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int W, void *stream,
-                                    fscnn_input_t **out)
+// Dense N x C x H x W activations -> compressed handle; synchronises st twice (the number of
+// stored values sizes the buffers), so x may be released as soon as this returns.
+static fscnn_status_t compress_activations(const float *x_dev, int N, int C, int H, int W,
+                                           hipStream_t st, fscnn_input_t **out)
 {
-    if (!x_dev || !out) return FSCNN_ERR_NULL;
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return FSCNN_ERR_SHAPE;
     const long long npix = (long long)N * H * W;
     if (!fits_int(npix + 1) || !fits_int(npix * C)) return FSCNN_ERR_SHAPE;
@@ -475,8 +476,6 @@ fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int
     int dev;
     fscnn_status_t s = have_device(&dev);
     if (s != FSCNN_OK) return s;
-    hipStream_t st = (hipStream_t)stream;
-
     fscnn_input_t *in = new (std::nothrow) fscnn_input();
     if (!in) return FSCNN_ERR_ALLOC;
     in->magic = kInputMagic;
@@ -519,6 +518,45 @@ fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int
     }
     *out = in;
     return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int W, void *stream,
+                                    fscnn_input_t **out)
+{
+    if (!x_dev || !out) return FSCNN_ERR_NULL;
+    return compress_activations(x_dev, N, C, H, W, (hipStream_t)stream, out);
+}
+
+fscnn_status_t fscnn_conv2d_sparse_filter_emit(fscnn_filter_t *f, const float *x_dev, int N, int C,
+                                               int H, int W, int sh, int sw, int ph, int pw,
+                                               const float *bias_dev, int relu, float *y_dev,
+                                               void *stream, fscnn_input_t **out)
+{
+    if (!f || !x_dev || !out) return FSCNN_ERR_NULL;
+    if (!live(f)) return FSCNN_ERR_HANDLE;
+    if (N <= 0 || C <= 0) return FSCNN_ERR_SHAPE;
+    int Ho, Wo;
+    fscnn_status_t s = out_shape(H, W, f->R, f->S, sh, sw, ph, pw, &Ho, &Wo);
+    if (s != FSCNN_OK) return s;
+    if (!fits_int((long long)N * f->K * Ho * Wo)) return FSCNN_ERR_UNSUPPORTED;
+    float *tmp = nullptr;
+    if (!y_dev) {
+        int dev;
+        s = have_device(&dev);
+        if (s != FSCNN_OK) return s;
+        if (hipMalloc(&tmp, sizeof(float) * (size_t)N * f->K * Ho * Wo) != hipSuccess) {
+            (void)hipGetLastError();
+            return FSCNN_ERR_ALLOC;
+        }
+    }
+    float *y = y_dev ? y_dev : tmp;
+    s = conv_sf_common(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, relu, y, FSCNN_LAYOUT_NCHW,
+                       FSCNN_LAYOUT_NCHW, 0, 0, stream);
+    // the compression ends with a synchronisation of the stream: the temporary is idle after it
+    if (s == FSCNN_OK) s = compress_activations(y, N, f->K, Ho, Wo, (hipStream_t)stream, out);
+    else if (tmp) (void)hipStreamSynchronize((hipStream_t)stream);
+    if (tmp) (void)hipFree(tmp);
+    return s;
 }
 
 fscnn_status_t fscnn_input_info(const fscnn_input_t *in, int *N, int *C, int *H, int *W,

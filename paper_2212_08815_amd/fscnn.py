@@ -25,6 +25,7 @@ EXPORTS = [
     "fscnn_filter_export", "fscnn_filter_prepare", "fscnn_filter_plan_export",
     "fscnn_filter_destroy", "fscnn_sf_variant_count", "fscnn_sf_variant_name", "fscnn_sf_variant_choice",
     "fscnn_conv2d_sparse_filter", "fscnn_conv2d_sparse_filter_v", "fscnn_input_compress",
+    "fscnn_conv2d_sparse_filter_emit",
     "fscnn_input_info", "fscnn_input_export", "fscnn_input_destroy", "fscnn_conv2d_sparse_input",
     "fscnn_maxpool2x2", "fscnn_conv2d_sparse_filter_ex", "fscnn_layout_convert",
     "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2", "fscnn_probe_gather_fma",
@@ -306,6 +307,32 @@ def input_compress(x):
     nnz = ctypes.c_longlong()
     _check(lib().fscnn_input_info(h, None, None, None, None, ctypes.byref(nnz)), "fscnn_input_info")
     return SparseInput(h, (N, C, H, W), nnz.value)
+
+
+def conv2d_sparse_filter_emit(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=False, dense_out=None):
+    """fscnn_conv2d_sparse_filter_emit: NCHW x -> SparseInput holding the non-zero results of the
+    convolution.  dense_out, if given (N x K x Ho x Wo), also receives the dense result."""
+    x = _dev_f32(x, "x")
+    bias = _dev_f32(bias, "bias")
+    if x.dim() != 4:
+        raise TypeError("x must be N x C x H x W")
+    N, C, H, W = x.shape
+    K, _, R, S = f.shape
+    Ho, Wo = conv2d_out_shape(H, W, R, S, stride, pad)
+    if dense_out is not None:
+        _dev_f32(dense_out, "dense_out")
+        if tuple(dense_out.shape) != (N, K, Ho, Wo):
+            raise TypeError("dense_out has the wrong shape")
+    if bias is not None and bias.numel() != K:
+        raise TypeError("bias must have K entries")
+    h = ctypes.c_void_p()
+    _check(lib().fscnn_conv2d_sparse_filter_emit(
+        f.handle, _ptr(x), _i(N), _i(C), _i(H), _i(W), _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]),
+        _ptr(bias), _i(bool(relu)), _ptr(dense_out), _stream(), ctypes.byref(h)),
+        "fscnn_conv2d_sparse_filter_emit")
+    nnz = ctypes.c_longlong()
+    _check(lib().fscnn_input_info(h, None, None, None, None, ctypes.byref(nnz)), "fscnn_input_info")
+    return SparseInput(h, (N, K, Ho, Wo), nnz.value)
 
 
 def input_export(s):

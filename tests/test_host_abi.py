@@ -55,6 +55,9 @@ def test_argument_checks_come_before_device_work(L):
     assert L.fscnn_input_compress(None, 1, 1, 1, 1, None, ctypes.byref(h)) == 1
     assert L.fscnn_input_compress(fake, 1, 1, 0, 1, None, ctypes.byref(h)) == 2
     assert L.fscnn_filter_destroy(None) == 1 and L.fscnn_input_destroy(None) == 1
+    assert L.fscnn_conv2d_sparse_filter_emit(None, fake, 1, 1, 4, 4, 1, 1, 0, 0, None, 0, None, None,
+                                             ctypes.byref(h)) == 1
+    assert L.fscnn_conv2d_sparse_filter_emit(fake, fake, 1, 1, 4, 4, 1, 1, 0, 0, None, 0, None, None, None) == 1
     assert L.fscnn_maxpool2x2(None, 1, 1, 2, 2, fake, None) == 1
     assert L.fscnn_maxpool2x2(fake, 1, 1, 1, 2, fake, None) == 2
     assert L.fscnn_conv2d_sparse_filter(None, fake, 1, 1, 4, 4, 1, 1, 0, 0, None, 0, fake, None) == 1
