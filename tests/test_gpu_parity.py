@@ -550,6 +550,31 @@ def test_config5_sparsity_sweep_sampled(F, keep):
     assert_parity(y.ravel()[flat], o, a, row_nmax(c["w"]), "config5 keep %g" % keep)
 
 
+# ------------------------------------------------------------------ largest sizes
+@pytest.mark.parametrize("wd,tiled", [(4095, True), (4096, False)])
+def test_largest_image_the_tiled_kernel_addresses(F, wd, tiled):
+    """The tiled kernel addresses the channels of four images with 32-bit byte offsets, i.e.
+    C*H*W*16 below 2^31: an 8-channel 4096 x 4095 image is the last one it takes (2.1 GB per
+    tensor at N=4), 4096 x 4096 goes to the direct kernel.  Sampled outputs, with the highest
+    addresses of every image among them."""
+    n, c, k, h = 4, 8, 8, 4096
+    rng = np.random.default_rng([77, wd])
+    x = rng.standard_normal((n, c, h, wd), dtype=np.float32)
+    w = np.where(rng.random((k, c, 3, 3)) < 0.5, rng.standard_normal((k, c, 3, 3)), 0).astype(np.float32)
+    b = rng.standard_normal(k, dtype=np.float32)
+    f = F.filter_compress(dev(w))
+    p = F.filter_plan_export(f, n, h, wd, (1, 1), (1, 1))
+    assert p["direct"] == (not tiled)
+    y = F.conv2d_sparse_filter(f, dev(x), (1, 1), (1, 1), dev(b), True)
+    per = k * h * wd
+    tail = np.concatenate([np.arange(per - 600, per) + i * per for i in range(n)])
+    head = np.concatenate([np.arange(600) + i * per for i in range(n)])
+    flat = np.unique(np.concatenate([tail, head, rng.choice(n * per, 4000, replace=False)]))
+    g = host(y.view(-1)[torch.from_numpy(flat).cuda()])
+    o, a = oracle.conv2d_points(x, w, flat, (1, 1), (1, 1), b, True, want_abs=True)
+    assert_parity(g, o, a, row_nmax(w), "largest image, W=%d" % wd)
+
+
 # ------------------------------------------------------------------ YOLO-shaped stack (second workload)
 def test_yolo_shaped_stack_chain(F):
     """Darknet-53's 52 convolutions as a chain (3x3 stride 1 and 2, 1x1, LeakyReLU 0.1), reduced
