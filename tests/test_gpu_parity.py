@@ -720,6 +720,32 @@ def test_config5_sparse_input_point(F):
         assert_parity(yp.ravel()[flat], o, a, 512 * 9, "config5 prepared sparse input variant %d" % v)
 
 
+def test_sparse_input_path_on_a_large_image(F):
+    """4.5 M pixel rows, about 20 M stored values: compression bit-exact, the convolution on
+    sampled outputs (first and last rows of the images among them), every configuration."""
+    n, c, k, h, wd = 2, 16, 32, 1500, 1501
+    rng = np.random.default_rng(78)
+    x = np.where(rng.random((n, c, h, wd)) < 0.7, 0, rng.standard_normal((n, c, h, wd))).astype(np.float32)
+    w = rng.standard_normal((k, c, 3, 3), dtype=np.float32)
+    b = rng.standard_normal(k, dtype=np.float32)
+    s = F.input_compress(dev(x))
+    op, oc, ov = oracle.input_compress(x)
+    prow, cidx, val = F.input_export(s)
+    assert np.array_equal(prow, op) and np.array_equal(cidx, oc) and np.array_equal(bits(val), bits(ov))
+    per = k * h * wd
+    flat = np.unique(np.concatenate([np.arange(per - 500, per) + i * per for i in range(n)] +
+                                    [np.arange(500) + i * per for i in range(n)] +
+                                    [rng.choice(n * per, 3000, replace=False)]))
+    o, a = oracle.conv2d_points(x, w, flat, (1, 1), (1, 1), b, True, want_abs=True)
+    d = F.dense_filter_prepare(dev(w))
+    fl = torch.from_numpy(flat).cuda()
+    for v in range(0, F.si_variant_count() + 1):
+        y = F.conv2d_sparse_input_prepared(s, d, (1, 1), (1, 1), dev(b), True, variant=v)
+        assert_parity(host(y.view(-1)[fl]), o, a, c * 9, "large image, prepared sparse input, variant %d" % v)
+    y = F.conv2d_sparse_input(s, dev(w), (1, 1), (1, 1), dev(b), True)
+    assert_parity(host(y.view(-1)[fl]), o, a, c * 9, "large image, sparse input")
+
+
 # ------------------------------------------------------------------ helper
 def test_maxpool_helper(F):
     x = np.random.default_rng(1).standard_normal((2, 5, 13, 22)).astype(np.float32)
