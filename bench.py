@@ -386,6 +386,14 @@ def main():
         conv_kernels_ms=conv_ms, conv_only_effective_gflops=F / (conv_ms * 1e-3) / 1e9,
         layer_ms=[round(v, 4) for v in layer_ms],
         layer_effective_tflops=[round(feff[i] / (layer_ms[i] * 1e-3) / 1e12, 2) for i in range(len(layer_ms))],
+        # per layer: the launch's bytes over time, and the time of the roof that binds it -- HBM
+        # (bytes / 8 TB/s) or the plain fp32 multiply-add rate, which is also the LDS rate of one
+        # word per multiply-add (flop / 78.6 TFLOP/s) -- as a share of the measured time
+        layer_launched_gbs=[round(blaunch[i] / (layer_ms[i] * 1e-3) / 1e9, 1) for i in range(len(layer_ms))],
+        layer_roof=[("hbm" if blaunch[i] / (HBM_PEAK_GBS * 1e9) > feff[i] / (FP32_UNPACKED_PEAK_TFLOPS * 1e12)
+                     else "alu/lds") for i in range(len(layer_ms))],
+        layer_roof_frac=[round(max(blaunch[i] / (HBM_PEAK_GBS * 1e9), feff[i] / (FP32_UNPACKED_PEAK_TFLOPS * 1e12))
+                               / (layer_ms[i] * 1e-3), 3) for i in range(len(layer_ms))],
         filter_compress_ms_all_layers=compress_ms,
         roofline=roofline,
     )
