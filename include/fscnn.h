@@ -200,7 +200,11 @@ fscnn_status_t fscnn_layout_convert(const float *src_dev, int N, int C, int H, i
 /* ------------------------------------------------------------------ sparse inputs
  * Activation compression (Sec. 3, sparse 3-D tensor in order O_chw: the channel run is the
  * innermost list): one row per pixel in (n, iy, ix) raster order holding the (channel,
- * value) pairs with x != 0.0f, channel ascending.  Synchronises `stream` once. */
+ * value) pairs with x != 0.0f, channel ascending.  Allocates the handle's buffers and
+ * synchronises `stream` once (the number of stored values sizes them).  The pass that writes
+ * the pairs is still queued on `stream` when the call returns: x_dev must stay valid until
+ * the work queued on `stream` so far has run (stream order suffices), and the library
+ * orders every later use of the handle, on any stream, behind that pass. */
 fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int W,
                                     void *stream, fscnn_input_t **out);
 fscnn_status_t fscnn_input_info(const fscnn_input_t *in, int *N, int *C, int *H, int *W,
@@ -217,8 +221,10 @@ fscnn_status_t fscnn_input_destroy(fscnn_input_t *in);
  * fscnn_input_compress would: a handle of shape N x K x Ho x Wo whose pixel rows list the
  * (channel, value) pairs with y != 0.0f.  y_dev may be NULL; if it is not, the dense
  * N x K x Ho x Wo result is left there as well (caller-owned, must not alias x).  With
- * y_dev NULL the call allocates and frees a dense temporary of that size.  Allocates the
- * handle's buffers and synchronises `stream` (the number of stored values sizes them);
+ * y_dev NULL the call allocates and frees a dense temporary of that size (and waits for
+ * `stream` before freeing it).  Allocates the handle's buffers and synchronises `stream`
+ * (the number of stored values sizes them); with y_dev given, x_dev and y_dev must stay
+ * valid until the work queued on `stream` has run, as for fscnn_input_compress;
  * *out is owned by the caller (fscnn_input_destroy).  Errors as the two calls it stands
  * for; on error *out is untouched. */
 fscnn_status_t fscnn_conv2d_sparse_filter_emit(fscnn_filter_t *f, const float *x_dev, int N, int C,

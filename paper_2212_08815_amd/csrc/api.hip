@@ -143,6 +143,13 @@ fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int
     return FSCNN_OK;
 }
 
+// Orders work on `st` behind the pass that fills a compressed-activation handle (it runs on the
+// stream the handle was made on and may still be in flight).
+hipError_t after_fill(const fscnn_input_t *in, hipStream_t st)
+{
+    return st == in->made_on ? hipSuccess : hipStreamWaitEvent(st, in->filled, 0);
+}
+
 fscnn_status_t check_conv_args(const fscnn_filter_t *f, const float *x, int N, int C, int H, int W,
                                int sh, int sw, int ph, int pw, const float *y, int *Ho, int *Wo)
 {
@@ -463,8 +470,9 @@ fscnn_status_t fscnn_conv2d_sparse_filter(fscnn_filter_t *f, const float *x_dev,
                                         0, stream);
 }
 
-// Dense N x C x H x W activations -> compressed handle; synchronises st twice (the number of
-// stored values sizes the buffers), so x may be released as soon as this returns.
+// Dense N x C x H x W activations -> compressed handle.  Synchronises st once (the number of
+// stored values sizes the second buffer); the pass that fills the handle is still running on st
+// when this returns, and reads x.
 static fscnn_status_t compress_activations(const float *x_dev, int N, int C, int H, int W,
                                            hipStream_t st, fscnn_input_t **out)
 {
@@ -483,35 +491,46 @@ static fscnn_status_t compress_activations(const float *x_dev, int N, int C, int
     in->N = N; in->C = C; in->H = H; in->W = W;
     in->nnz = 0; in->CC = CC; in->NCH = NCH;
     in->cidx = nullptr; in->xval = nullptr; in->cptr = nullptr;
-    int *cnt = nullptr;
+    in->ptr_block = nullptr; in->node_block = nullptr;
+    in->made_on = st; in->filled = nullptr;
     int total = 0;
     const long long nstep = npix * NCH;   // (pixel, channel step) pairs
-    hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)(nstep + scan_tmp_elems(nstep)));
-    if (e == hipSuccess) e = hipMalloc(&in->cptr, sizeof(int) * (size_t)(nstep + 1));
-    if (e == hipSuccess) e = launch_input_count(x_dev, N, C, H, W, CC, NCH, cnt, st);
-    if (e == hipSuccess) e = launch_exclusive_scan(cnt, in->cptr, nstep, cnt + nstep, st);
+    // first allocation: the pointer array, then (256-byte aligned) the counts it is scanned from
+    // and the scan's scratch; the counts stay with the handle, so nothing is freed here
+    const size_t cnt_at = ((size_t)(nstep + 1) * sizeof(int) + 255) / 256 * 256;
+    hipError_t e = hipMalloc(&in->ptr_block, cnt_at + sizeof(int) * (size_t)(nstep + scan_tmp_elems(nstep)));
+    if (e == hipSuccess) {
+        in->cptr = static_cast<int *>(in->ptr_block);
+        int *cnt = reinterpret_cast<int *>(static_cast<char *>(in->ptr_block) + cnt_at);
+        e = launch_input_count(x_dev, N, C, H, W, CC, NCH, cnt, st);
+        if (e == hipSuccess) e = launch_exclusive_scan(cnt, in->cptr, nstep, cnt + nstep, st);
+    }
     if (e == hipSuccess)
         e = hipMemcpyAsync(&total, in->cptr + nstep, sizeof(int), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e == hipSuccess) {
         in->nnz = total;
-        // spare entries: the sparse-input kernels fetch the next (channel, value) pairs of a
-        // pixel's list ahead, up to kSiSpare positions past the one in use
+        // second allocation: indices, then (256-byte aligned) values.  Spare entries: the
+        // sparse-input kernels fetch the next (channel, value) pairs of a pixel's list ahead, up
+        // to kSiSpare positions past the one in use
         const size_t n = (size_t)total + kSiSpare;
-        e = hipMalloc(&in->cidx, sizeof(uint32_t) * n);
-        if (e == hipSuccess) e = hipMalloc(&in->xval, sizeof(float) * n);
-        if (e == hipSuccess) e = hipMemsetAsync(in->cidx + total, 0, sizeof(uint32_t) * kSiSpare, st);
-        if (e == hipSuccess) e = hipMemsetAsync(in->xval + total, 0, sizeof(float) * kSiSpare, st);
+        const size_t val_at = (n * sizeof(uint32_t) + 255) / 256 * 256;
+        e = hipMalloc(&in->node_block, val_at + n * sizeof(float));
+        if (e == hipSuccess) {
+            in->cidx = static_cast<uint32_t *>(in->node_block);
+            in->xval = reinterpret_cast<float *>(static_cast<char *>(in->node_block) + val_at);
+            e = launch_input_fill(x_dev, N, C, H, W, CC, NCH, in->cptr, in->cidx, in->xval, total,
+                                  kSiSpare, st);
+        }
     }
-    if (e == hipSuccess)
-        e = launch_input_fill(x_dev, N, C, H, W, CC, NCH, in->cptr, in->cidx, in->xval, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (cnt) (void)hipFree(cnt);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&in->filled, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventRecord(in->filled, st);
     if (e != hipSuccess) {
         (void)hipGetLastError();
-        if (in->cptr) (void)hipFree(in->cptr);
-        if (in->cidx) (void)hipFree(in->cidx);
-        if (in->xval) (void)hipFree(in->xval);
+        (void)hipStreamSynchronize(st);   // nothing may still write into what is freed next
+        if (in->filled) (void)hipEventDestroy(in->filled);
+        if (in->ptr_block) (void)hipFree(in->ptr_block);
+        if (in->node_block) (void)hipFree(in->node_block);
         in->magic = 0;
         delete in;
         return e == hipErrorOutOfMemory ? FSCNN_ERR_ALLOC : FSCNN_ERR_DEVICE;
@@ -552,10 +571,12 @@ fscnn_status_t fscnn_conv2d_sparse_filter_emit(fscnn_filter_t *f, const float *x
     float *y = y_dev ? y_dev : tmp;
     s = conv_sf_common(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, relu, y, FSCNN_LAYOUT_NCHW,
                        FSCNN_LAYOUT_NCHW, 0, 0, stream);
-    // the compression ends with a synchronisation of the stream: the temporary is idle after it
     if (s == FSCNN_OK) s = compress_activations(y, N, f->K, Ho, Wo, (hipStream_t)stream, out);
-    else if (tmp) (void)hipStreamSynchronize((hipStream_t)stream);
-    if (tmp) (void)hipFree(tmp);
+    if (tmp) {
+        // the last pass over the temporary may still be running
+        (void)hipStreamSynchronize((hipStream_t)stream);
+        (void)hipFree(tmp);
+    }
     return s;
 }
 
@@ -578,6 +599,7 @@ fscnn_status_t fscnn_input_export(const fscnn_input_t *in, int *prow_host, unsig
     if (!in || !prow_host) return FSCNN_ERR_NULL;
     if (!live(in)) return FSCNN_ERR_HANDLE;
     if (in->nnz > 0 && (!cidx_host || !val_host)) return FSCNN_ERR_NULL;
+    FSCNN_HIP(hipEventSynchronize(in->filled));
     // the row pointers are every NCH-th chunk pointer
     const size_t npix = (size_t)in->N * in->H * in->W;
     FSCNN_HIP(hipMemcpy2D(prow_host, sizeof(int), in->cptr, sizeof(int) * (size_t)in->NCH, sizeof(int), npix,
@@ -595,9 +617,10 @@ fscnn_status_t fscnn_input_destroy(fscnn_input_t *in)
     if (!in) return FSCNN_ERR_NULL;
     if (!live(in)) return FSCNN_ERR_HANDLE;
     in->magic = 0;
-    if (in->cptr) (void)hipFree(in->cptr);
-    if (in->cidx) (void)hipFree(in->cidx);
-    if (in->xval) (void)hipFree(in->xval);
+    (void)hipEventSynchronize(in->filled);
+    (void)hipEventDestroy(in->filled);
+    if (in->ptr_block) (void)hipFree(in->ptr_block);
+    if (in->node_block) (void)hipFree(in->node_block);
     delete in;
     return FSCNN_OK;
 }
@@ -617,6 +640,7 @@ fscnn_status_t fscnn_conv2d_sparse_input(const fscnn_input_t *in, const float *w
     int dev;
     s = have_device(&dev);
     if (s != FSCNN_OK) return s;
+    FSCNN_HIP(after_fill(in, (hipStream_t)stream));
     FSCNN_HIP(launch_conv_si(in, w_dev, K, R, S, Ho, Wo, sh, sw, ph, pw, bias_dev, relu, y_dev,
                              (hipStream_t)stream));
     return FSCNN_OK;
@@ -681,6 +705,7 @@ fscnn_status_t fscnn_conv2d_sparse_input_prepared(const fscnn_input_t *in, const
     int dev;
     s = have_device(&dev);
     if (s != FSCNN_OK) return s;
+    FSCNN_HIP(after_fill(in, (hipStream_t)stream));
     FSCNN_HIP(launch_conv_si_prepared(in, d, Ho, Wo, ph, pw, bias_dev, relu, y_dev, variant,
                                       (hipStream_t)stream));
     return FSCNN_OK;

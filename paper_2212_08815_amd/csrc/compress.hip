@@ -291,10 +291,16 @@ __global__ void __launch_bounds__(kBlock) input_fill_kernel(const float *__restr
                                                             long long HW, long long npix, int CC,
                                                             int NCH, const int *__restrict__ cptr,
                                                             uint32_t *__restrict__ cidx,
-                                                            float *__restrict__ xval)
+                                                            float *__restrict__ xval, long long total,
+                                                            int spare)
 {
     const long long p = (long long)blockIdx.x * kBlock + threadIdx.x;
     const int j = blockIdx.y;
+    // the entries past the last stored one (readers fetch a few positions ahead)
+    if (blockIdx.x == 0 && j == 0 && (int)threadIdx.x < spare) {
+        cidx[total + threadIdx.x] = 0u;
+        xval[total + threadIdx.x] = 0.0f;
+    }
     if (p >= npix) return;
     const long long n = p / HW, q = p % HW;
     const float *xp = x + n * C * HW + q;
@@ -440,11 +446,13 @@ hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int CC
 }
 
 hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, int CC, int NCH,
-                             const int *cptr, uint32_t *cidx, float *xval, hipStream_t st)
+                             const int *cptr, uint32_t *cidx, float *xval, long long total, int spare,
+                             hipStream_t st)
 {
     const long long HW = (long long)H * W, npix = (long long)N * HW;
+    if (spare > kBlock) return hipErrorInvalidValue;
     hipLaunchKernelGGL(input_fill_kernel, dim3(blocks_for(npix, kBlock), NCH), dim3(kBlock), 0, st, x, C,
-                       HW, npix, CC, NCH, cptr, cidx, xval);
+                       HW, npix, CC, NCH, cptr, cidx, xval, total, spare);
     return hipGetLastError();
 }
 

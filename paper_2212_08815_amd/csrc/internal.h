@@ -102,6 +102,13 @@ struct fscnn_input {
     float *xval;     // device [nnz]
     int *cptr;       // device [N*H*W*NCH + 1]: cptr[p*NCH + j] = first entry of pixel p with
                      // c >= j*CC; pixel p's row is [cptr[p*NCH], cptr[(p+1)*NCH])
+    // the two device allocations behind the arrays: pointers (and the counts they were scanned
+    // from), then indices and values
+    void *ptr_block, *node_block;
+    // the pass that fills the handle runs on `made_on` and may still be in flight when the
+    // handle is returned; `filled` is recorded behind it, for users on other streams
+    hipStream_t made_on;
+    hipEvent_t filled;
 };
 
 // Dense filter bank prepared for the sparse-input convolution: a K-contiguous copy
@@ -129,8 +136,10 @@ hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float 
                             hipStream_t st);
 hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int CC, int NCH, int *cnt,
                               hipStream_t st);
+// also zeroes the `spare` entries that follow the last stored one
 hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, int CC, int NCH,
-                             const int *cptr, uint32_t *cidx, float *xval, hipStream_t st);
+                             const int *cptr, uint32_t *cidx, float *xval, long long total, int spare,
+                             hipStream_t st);
 hipError_t launch_maxpool2x2(const float *x, int N, int C, int H, int W, float *y, int n4,
                              hipStream_t st);
 hipError_t launch_layout_convert(const float *src, int N, int C, int H, int W, int src_n4, float *dst,

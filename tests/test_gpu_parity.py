@@ -720,6 +720,26 @@ def test_config5_sparse_input_point(F):
         assert_parity(yp.ravel()[flat], o, a, 512 * 9, "config5 prepared sparse input variant %d" % v)
 
 
+def test_compressed_input_is_usable_from_another_stream(F):
+    """The pass that fills a compressed handle is still queued when fscnn_input_compress returns;
+    a convolution launched on a different stream must be ordered behind it by the library."""
+    x, w, b = inputs.random_layer(96, 4, 64, 64, 56, 56, 3, 3, keep=1.0, x_zero_frac=0.6)
+    xd, wd, bd = dev(x), dev(w), dev(b)
+    d = F.dense_filter_prepare(wd)
+    torch.cuda.synchronize()
+    want = host(F.conv2d_sparse_input_prepared(F.input_compress(xd), d, (1, 1), (1, 1), bd, True))
+    other = torch.cuda.Stream()
+    for _ in range(5):
+        s = F.input_compress(xd)                      # made on the current stream
+        with torch.cuda.stream(other):
+            y = F.conv2d_sparse_input_prepared(s, d, (1, 1), (1, 1), bd, True)
+        other.synchronize()
+        assert np.array_equal(host(y), want)
+        prow, cidx, val = F.input_export(s)           # export waits for the fill as well
+        assert prow[-1] == s.nnz == cidx.size
+    torch.cuda.synchronize()
+
+
 def test_sparse_input_path_on_a_large_image(F):
     """4.5 M pixel rows, about 20 M stored values: compression bit-exact, the convolution on
     sampled outputs (first and last rows of the images among them), every configuration."""
