@@ -200,7 +200,8 @@ fscnn_status_t fscnn_layout_convert(const float *src_dev, int N, int C, int H, i
 /* ------------------------------------------------------------------ sparse inputs
  * Activation compression (Sec. 3, sparse 3-D tensor in order O_chw: the channel run is the
  * innermost list): one row per pixel in (n, iy, ix) raster order holding the (channel,
- * value) pairs with x != 0.0f, channel ascending.  Allocates the handle's buffers and
+ * value) pairs with x != 0.0f, channel ascending.  C up to 8192 (beyond:
+ * FSCNN_ERR_UNSUPPORTED).  Allocates the handle's buffers and
  * synchronises `stream` once (the number of stored values sizes them).  The pass that writes
  * the pairs is still queued on `stream` when the call returns: x_dev must stay valid until
  * the work queued on `stream` so far has run (stream order suffices), and the library

@@ -480,7 +480,8 @@ static fscnn_status_t compress_activations(const float *x_dev, int N, int C, int
     const long long npix = (long long)N * H * W;
     if (!fits_int(npix + 1) || !fits_int(npix * C)) return FSCNN_ERR_SHAPE;
     const int CC = kSiCC, NCH = (C + CC - 1) / CC;
-    if (!fits_int(npix * NCH + 1) || NCH > 65535) return FSCNN_ERR_UNSUPPORTED;
+    // the packing pass keeps a pixel's whole list in LDS: up to 8192 channels
+    if (!fits_int(npix * NCH + 1) || NCH > 8192 / kSiCC) return FSCNN_ERR_UNSUPPORTED;
     int dev;
     fscnn_status_t s = have_device(&dev);
     if (s != FSCNN_OK) return s;

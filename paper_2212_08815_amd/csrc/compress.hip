@@ -287,32 +287,52 @@ __global__ void __launch_bounds__(kBlock) input_count_kernel(const float *__rest
     cnt[p * NCH + j] = c;
 }
 
+// A work-group packs the lists of PX consecutive pixels (PX a power of two, at most 32): thread
+// (pixel px, step lane sj) walks the steps sj, sj + 256/PX, ... of its pixel, so the reads of a
+// channel plane cover PX adjacent floats, and drops its (channel, value) pairs into an LDS image
+// of the group's output range -- the lists of consecutive pixels are adjacent in memory -- which
+// is then copied out with fully coalesced stores.
 __global__ void __launch_bounds__(kBlock) input_fill_kernel(const float *__restrict__ x, int C,
                                                             long long HW, long long npix, int CC,
-                                                            int NCH, const int *__restrict__ cptr,
+                                                            int NCH, int PX,
+                                                            const int *__restrict__ cptr,
                                                             uint32_t *__restrict__ cidx,
                                                             float *__restrict__ xval, long long total,
                                                             int spare)
 {
-    const long long p = (long long)blockIdx.x * kBlock + threadIdx.x;
-    const int j = blockIdx.y;
+    extern __shared__ uint32_t stage[];   // [cap] channel indices, then [cap] value bit patterns
+    const int cap = PX * NCH * CC;
     // the entries past the last stored one (readers fetch a few positions ahead)
-    if (blockIdx.x == 0 && j == 0 && (int)threadIdx.x < spare) {
+    if (blockIdx.x == 0 && (int)threadIdx.x < spare) {
         cidx[total + threadIdx.x] = 0u;
         xval[total + threadIdx.x] = 0.0f;
     }
-    if (p >= npix) return;
-    const long long n = p / HW, q = p % HW;
-    const float *xp = x + n * C * HW + q;
-    const int c1 = (j + 1) * CC < C ? (j + 1) * CC : C;
-    int o = cptr[p * NCH + j];
-    for (int ch = j * CC; ch < c1; ++ch) {
-        const float v = xp[(long long)ch * HW];
-        if (v != 0.0f) {
-            cidx[o] = (uint32_t)ch;
-            xval[o] = v;
-            ++o;
+    const long long p0 = (long long)blockIdx.x * PX;
+    const long long p1 = p0 + PX < npix ? p0 + PX : npix;
+    const int base = cptr[p0 * NCH];
+    const int count = cptr[p1 * NCH] - base;      // <= cap: at most C entries per pixel
+    const int px = threadIdx.x % PX, sj = threadIdx.x / PX;
+    const long long p = p0 + px;
+    if (p < npix) {
+        const long long n = p / HW, q = p % HW;
+        const float *xp = x + n * C * HW + q;
+        for (int j = sj; j < NCH; j += kBlock / PX) {
+            const int c1 = (j + 1) * CC < C ? (j + 1) * CC : C;
+            int o = cptr[p * NCH + j] - base;
+            for (int ch = j * CC; ch < c1; ++ch) {
+                const float v = xp[(long long)ch * HW];
+                if (v != 0.0f) {
+                    stage[o] = (uint32_t)ch;
+                    stage[cap + o] = __float_as_uint(v);
+                    ++o;
+                }
+            }
         }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < count; t += kBlock) {
+        cidx[base + t] = stage[t];
+        xval[base + t] = __uint_as_float(stage[cap + t]);
     }
 }
 
@@ -451,8 +471,14 @@ hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, int CC,
 {
     const long long HW = (long long)H * W, npix = (long long)N * HW;
     if (spare > kBlock) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(input_fill_kernel, dim3(blocks_for(npix, kBlock), NCH), dim3(kBlock), 0, st, x, C,
-                       HW, npix, CC, NCH, cptr, cidx, xval, total, spare);
+    // pixels per work-group: as many (up to 32) as keep the LDS image of their lists, 8 bytes per
+    // possible entry, within 64 KB
+    int PX = 32;
+    while (PX > 1 && (long long)PX * NCH * CC * 8 > 65536) PX /= 2;
+    const long long lds = (long long)PX * NCH * CC * 8;
+    if (lds > 65536) return hipErrorInvalidValue;   // more than 8192 channels: not served
+    hipLaunchKernelGGL(input_fill_kernel, dim3(blocks_for(npix, PX)), dim3(kBlock), (size_t)lds, st, x, C,
+                       HW, npix, CC, NCH, PX, cptr, cidx, xval, total, spare);
     return hipGetLastError();
 }
 

@@ -54,6 +54,7 @@ def test_argument_checks_come_before_device_work(L):
     assert L.fscnn_filter_compress(fake, 1 << 16, 1 << 16, 3, 3, None, ctypes.byref(h)) == 2
     assert L.fscnn_input_compress(None, 1, 1, 1, 1, None, ctypes.byref(h)) == 1
     assert L.fscnn_input_compress(fake, 1, 1, 0, 1, None, ctypes.byref(h)) == 2
+    assert L.fscnn_input_compress(fake, 1, 8193, 2, 2, None, ctypes.byref(h)) == 4      # more than 8192 channels
     assert L.fscnn_filter_destroy(None) == 1 and L.fscnn_input_destroy(None) == 1
     assert L.fscnn_conv2d_sparse_filter_emit(None, fake, 1, 1, 4, 4, 1, 1, 0, 0, None, 0, None, None,
                                              ctypes.byref(h)) == 1
