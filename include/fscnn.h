@@ -35,7 +35,7 @@ typedef enum {
     FSCNN_OK = 0,
     FSCNN_ERR_NULL = 1,        /* a required pointer is NULL                                   */
     FSCNN_ERR_SHAPE = 2,       /* non-positive size, negative pad, empty output, size overflow */
-    FSCNN_ERR_MISMATCH = 3,    /* x / w dimensions disagree with the handle                    */
+    FSCNN_ERR_MISMATCH = 3,    /* x / w dimensions, or the current device, disagree with the handle */
     FSCNN_ERR_UNSUPPORTED = 4, /* valid request outside what the kernels cover                 */
     FSCNN_ERR_ALLOC = 5,       /* device or host allocation failed                             */
     FSCNN_ERR_DEVICE = 6,      /* HIP runtime error (no device, launch failure, ...)           */

@@ -95,6 +95,14 @@ fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan *
         delete p;
         return FSCNN_ERR_UNSUPPORTED;
     }
+    // the plan is built next to the handle's arrays
+    int dev;
+    fscnn_status_t ds = have_device(&dev);
+    if (ds == FSCNN_OK && dev != f->device) ds = FSCNN_ERR_MISMATCH;
+    if (ds != FSCNN_OK) {
+        delete p;
+        return ds;
+    }
     int *cnt = nullptr;
     hipError_t e = hipMalloc(&cnt, sizeof(int) * (size_t)(nb + scan_tmp_elems(nb)));
     if (e == hipSuccess) e = hipMalloc(&p->segptr, sizeof(int) * (size_t)(nb + 1));
@@ -385,6 +393,7 @@ static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int 
     int dev;
     s = have_device(&dev);
     if (s != FSCNN_OK) return s;
+    if (dev != f->device) return FSCNN_ERR_MISMATCH;   // the handle's buffers live on another GPU
     hipStream_t st = (hipStream_t)stream;
     SfPlan *p;
     s = get_plan(f, v, st, &p);
@@ -641,6 +650,7 @@ fscnn_status_t fscnn_conv2d_sparse_input(const fscnn_input_t *in, const float *w
     int dev;
     s = have_device(&dev);
     if (s != FSCNN_OK) return s;
+    if (dev != in->device) return FSCNN_ERR_MISMATCH;
     FSCNN_HIP(after_fill(in, (hipStream_t)stream));
     FSCNN_HIP(launch_conv_si(in, w_dev, K, R, S, Ho, Wo, sh, sw, ph, pw, bias_dev, relu, y_dev,
                              (hipStream_t)stream));
@@ -706,6 +716,7 @@ fscnn_status_t fscnn_conv2d_sparse_input_prepared(const fscnn_input_t *in, const
     int dev;
     s = have_device(&dev);
     if (s != FSCNN_OK) return s;
+    if (dev != in->device || dev != d->device) return FSCNN_ERR_MISMATCH;
     FSCNN_HIP(after_fill(in, (hipStream_t)stream));
     FSCNN_HIP(launch_conv_si_prepared(in, d, Ho, Wo, ph, pw, bias_dev, relu, y_dev, variant,
                                       (hipStream_t)stream));
