@@ -136,7 +136,13 @@ def other_rows(fscnn, torch, inputs, np, dev_layers):
         y = fscnn.conv2d_sparse_filter(f, x, (1, 1), (1, 1), b, True)
         ms = time_gpu(torch, lambda: fscnn.conv2d_sparse_filter(f, x, (1, 1), (1, 1), b, True, out=y), 10)
         feff = 2.0 * f.nnz * 28 * 28 * 8
-        sweep.append(dict(keep=keep, nnz=f.nnz, ms=ms, effective_tflops=feff / ms / 1e9))
+        # the same launch on batch-interleaved (N4) tensors, as chained layers pass them
+        x4 = fscnn.layout_convert(x, fscnn.NCHW)
+        y4 = fscnn.conv2d_sparse_filter(f, x4, (1, 1), (1, 1), b, True, x_layout=fscnn.N4, y_layout=fscnn.N4, n=8)
+        ms4 = time_gpu(torch, lambda: fscnn.conv2d_sparse_filter(f, x4, (1, 1), (1, 1), b, True, out=y4,
+                                                                 x_layout=fscnn.N4, y_layout=fscnn.N4, n=8), 10)
+        sweep.append(dict(keep=keep, nnz=f.nnz, ms=ms, effective_tflops=feff / ms / 1e9,
+                          ms_n4=ms4, effective_tflops_n4=feff / ms4 / 1e9))
         if keep == 0.05:
             n, ch, h, wd = c["x"].shape
             ms_c = time_gpu(torch, lambda: fscnn.input_compress(x), 5)
