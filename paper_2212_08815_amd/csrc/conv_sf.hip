@@ -727,6 +727,7 @@ const Variant *variants(int *count)
         FSCNN_V4S2(32, 2, 4, 2, 16, 4, 1, 2),  // 23  32x8 tiles
         FSCNN_V4S2(16, 4, 2, 4, 16, 7, 1, 2),  // 24  16x8 tiles, 4 channels per wave
         FSCNN_V4S2(16, 4, 2, 2, 16, 7, 4, 2),  // 25  as 22, four records per trip
+        FSCNN_V4P(16, 4, 2, 4, 16, 12, 1, 2),  // 26  112x112 and 224x224: 16x8 tiles (widths 7*2^k without idle columns), 4 channels per wave
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
@@ -810,8 +811,8 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int strid
     // slots are faster (measured on the same stack at N = 1).
     if (N >= 4 || W <= 112) {
         if (W > 64 && C <= 8) { pref[0] = 1; pref[1] = 4; pref[2] = 3; pref[3] = 3; }
-        else if (W > 128) { pref[0] = 5; pref[1] = 4; pref[2] = 2; pref[3] = 3; }
-        else if (W > 64) { pref[0] = 4; pref[1] = 2; pref[2] = 3; pref[3] = 3; }
+        else if (W > 128) { pref[0] = 26; pref[1] = 5; pref[2] = 4; pref[3] = 3; }
+        else if (W > 64) { pref[0] = 26; pref[1] = 4; pref[2] = 2; pref[3] = 3; }
         else if (W > 32) { pref[0] = 6; pref[1] = 2; pref[2] = 4; pref[3] = 3; }
         else if (W > 16) { pref[0] = 6; pref[1] = 2; pref[2] = 4; pref[3] = 3; }
         else { pref[0] = 3; pref[1] = 9; pref[2] = 9; pref[3] = 9; }
