@@ -728,6 +728,11 @@ const Variant *variants(int *count)
         FSCNN_V4S2(16, 4, 2, 4, 16, 7, 1, 2),  // 24  16x8 tiles, 4 channels per wave
         FSCNN_V4S2(16, 4, 2, 2, 16, 7, 4, 2),  // 25  as 22, four records per trip
         FSCNN_V4P(16, 4, 2, 4, 16, 12, 1, 2),  // 26  112x112 and 224x224: 16x8 tiles (widths 7*2^k without idle columns), 4 channels per wave
+        FSCNN_V4S2(32, 2, 4, 4, 16, 4, 1, 2),  // 27  stride 2, outputs 17..64 wide: 32x8 tiles, 4 channels per wave
+        FSCNN_V4S2(16, 4, 2, 4, 16, 3, 1, 2),  // 28  stride 2, wider outputs: 16x8 tiles, 4 channels per wave, small chunks
+        FSCNN_V411(32, 2, 2, 4, 16, 40, 4, 2), // 29  1x1, 17..32 wide: 32x4 tiles, 40-channel chunks
+        FSCNN_V411(16, 4, 1, 4, 16, 80, 4, 2), // 30  1x1, up to 16 wide: 16x4 tiles, 80-channel chunks
+        FSCNN_V411(32, 2, 2, 2, 16, 20, 4, 2), // 31  1x1, wider than 128: 32x4 tiles, 2 channels per wave
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
@@ -794,13 +799,16 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int strid
     const Variant *t = variants(&n);
     if (stride == 2) {   // 3x3 only, four-image forms, no pooled form; H, W are the output's here
         if (R != 3 || S != 3 || pool) return 0;
+        const int first = W > 64 ? 28 : W > 16 ? 27 : 24;   // measured on Darknet-53's down-sampling layers, N = 32
+        if (sf_blocks(t[first - 1].g, N, K, H, W) >= 192) return first;
         return sf_blocks(t[24 - 1].g, N, K, H, W) >= 192 ? 24 : 22;
     }
     if (stride != 1) return 0;
     if (R == 1 && S == 1) {   // 1x1: four-image forms only, no pooled form
         if (pool) return 0;
-        const int cand[3] = {W > 16 ? 18 : 20, 20, 19};
-        for (int i = 0; i < 3; ++i)
+        // measured on Darknet-53's 1x1 layers, N = 32
+        const int cand[4] = {W > 128 ? 31 : W > 32 ? 18 : W > 16 ? 29 : 30, W > 16 ? 18 : 20, 20, 19};
+        for (int i = 0; i < 4; ++i)
             if (sf_blocks(t[cand[i] - 1].g, N, K, H, W) >= 192) return cand[i];
         return 20;
     }
