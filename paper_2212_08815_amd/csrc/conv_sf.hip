@@ -733,6 +733,7 @@ const Variant *variants(int *count)
         FSCNN_V411(32, 2, 2, 4, 16, 40, 4, 2), // 29  1x1, 17..32 wide: 32x4 tiles, 40-channel chunks
         FSCNN_V411(16, 4, 1, 4, 16, 80, 4, 2), // 30  1x1, up to 16 wide: 16x4 tiles, 80-channel chunks
         FSCNN_V411(32, 2, 2, 2, 16, 20, 4, 2), // 31  1x1, wider than 128: 32x4 tiles, 2 channels per wave
+        FSCNN_V4P(16, 4, 4, 2, 16, 15, 0, 2),  // 32  up to 16x16 images with many output channels: one 16x16 tile per image, pipelined
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
@@ -823,7 +824,7 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int strid
         else if (W > 64) { pref[0] = 26; pref[1] = 4; pref[2] = 2; pref[3] = 3; }
         else if (W > 32) { pref[0] = 6; pref[1] = 2; pref[2] = 4; pref[3] = 3; }
         else if (W > 16) { pref[0] = 6; pref[1] = 2; pref[2] = 4; pref[3] = 3; }
-        else { pref[0] = 3; pref[1] = 9; pref[2] = 9; pref[3] = 9; }
+        else { pref[0] = 32; pref[1] = 3; pref[2] = 9; pref[3] = 9; }
     } else {
         if (W > 32) { pref[0] = 11; pref[1] = 12; pref[2] = 13; pref[3] = 13; }
         else if (W > 16) { pref[0] = 12; pref[1] = 13; pref[2] = 13; pref[3] = 13; }
