@@ -262,7 +262,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--keep", type=float, default=0.05, help="weight density of layers 2..13")
     ap.add_argument("--cpu-images", type=int, default=16, help="images of the oracle-timed sample (0 = skip)")
@@ -338,6 +338,7 @@ def main():
     else:
         span = lambda s, li: events[s][li].elapsed_time(events[s][li + 1])
     layer_ms = [float(np.mean([span(s, li) for s in range(args.steps)])) for li in range(len(dev_layers))]
+    layer_ms_median = [float(np.median([span(s, li) for s in range(args.steps)])) for li in range(len(dev_layers))]
     conv_ms = sum(layer_ms)
     # dominant kernel = the instantiation (configuration, layouts, pooled or not) with the largest
     # share of the step; its figures are means over its launches
@@ -391,6 +392,7 @@ def main():
                  frac_of_peak=B / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, peak_gbs=HBM_PEAK_GBS),
         conv_kernels_ms=conv_ms, conv_only_effective_gflops=F / (conv_ms * 1e-3) / 1e9,
         layer_ms=[round(v, 4) for v in layer_ms],
+        layer_ms_median=[round(v, 4) for v in layer_ms_median],
         layer_effective_tflops=[round(feff[i] / (layer_ms[i] * 1e-3) / 1e12, 2) for i in range(len(layer_ms))],
         # per layer: the launch's bytes over time, and the time of the roof that binds it -- HBM
         # (bytes / 8 TB/s) or the plain fp32 multiply-add rate, which is also the LDS rate of one
