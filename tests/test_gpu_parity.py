@@ -720,6 +720,32 @@ def test_config5_sparse_input_point(F):
         assert_parity(yp.ravel()[flat], o, a, 512 * 9, "config5 prepared sparse input variant %d" % v)
 
 
+def test_filter_handle_serves_two_streams_at_once(F):
+    """One compressed filter, two streams launching convolutions on different inputs at the same
+    time (the plan is built once, under the handle's lock): both results equal the ones computed
+    one after the other."""
+    xa, w, b = inputs.random_layer(97, 8, 64, 96, 56, 56, 3, 3, keep=0.1)
+    xb = inputs.random_layer(98, 8, 64, 96, 56, 56, 3, 3, keep=0.1)[0]
+    f = F.filter_compress(dev(w))
+    xad, xbd, bd = dev(xa), dev(xb), dev(b)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for _ in range(4):
+        with torch.cuda.stream(s1):
+            ya = F.conv2d_sparse_filter(f, xad, (1, 1), (1, 1), bd, True)
+        with torch.cuda.stream(s2):
+            yb = F.conv2d_sparse_filter(f, xbd, (1, 1), (1, 1), bd, True)
+        outs.append((ya, yb))
+    s1.synchronize(); s2.synchronize()
+    wa = host(F.conv2d_sparse_filter(f, xad, (1, 1), (1, 1), bd, True))
+    wb = host(F.conv2d_sparse_filter(f, xbd, (1, 1), (1, 1), bd, True))
+    for ya, yb in outs:
+        assert np.array_equal(host(ya), wa) and np.array_equal(host(yb), wb)
+    o, a = oracle.conv2d_dense(xa, w, (1, 1), (1, 1), b, True, want_abs=True)
+    assert_parity(wa, o, a, row_nmax(w), "two streams, first input")
+
+
 def test_compressed_input_is_usable_from_another_stream(F):
     """The pass that fills a compressed handle is still queued when fscnn_input_compress returns;
     a convolution launched on a different stream must be ordered behind it by the library."""
