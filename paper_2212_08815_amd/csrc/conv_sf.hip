@@ -317,8 +317,12 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                 };
                 auto trip = [&](f4v(&cur)[G::NV], f4v(&nxt)[G::NV]) {
                     landed(cur);
+                    // the reads go out at raised priority: a wave that is ready to fetch is
+                    // served before the multiply-adds of the others, which keeps the LDS busy
+                    __builtin_amdgcn_s_setprio(3);
                     issue(nxt, q[1].off);
                     const Rec fresh = recs[i + 3];
+                    __builtin_amdgcn_s_setprio(0);
                     __builtin_amdgcn_sched_barrier(0);
                     mul(cur);
                     q[0] = q[1];
@@ -361,6 +365,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                 const int left = end - i;
                 const int ni = left < G::U ? end : i + G::U;
                 V in[G::U][G::NV];
+                __builtin_amdgcn_s_setprio(3);   // reads and refill at raised priority (see the pipelined loop)
 #pragma unroll
                 for (int m = 0; m < G::U; ++m) {
                     const char *p = tile + q[m].off;
@@ -371,6 +376,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                 Rec fresh[G::U];
 #pragma unroll
                 for (int m = 0; m < G::U; ++m) fresh[m] = recs[ni + m];
+                __builtin_amdgcn_s_setprio(0);
                 if constexpr (G::U > 1) {
 #pragma unroll
                     for (int m = 1; m < G::U; ++m)
