@@ -281,8 +281,8 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
             // Software pipeline (BV = 4).  Invariant at the top of a trip for record i:
             // q[0..2] = records i, i+1, i+2 and the taps of record i are in flight into `cur`.
             // A trip waits for them (and for the record fetched one trip ago), starts the reads
-            // of record i+1 into the other buffer and the fetch of record i+3, and only then
-            // multiplies record i: the LDS latency hides behind the multiply-adds of the same
+            // of record i+1 into the other buffer and the fetch of record i+3, and multiplies
+            // record i meanwhile: the LDS latency hides behind the multiply-adds of the same
             // wave.  Trips come in pairs (A then B), so every segment starts with its first
             // record in buffer A; a segment's odd last record is multiplied out of A and only
             // then are the next record's reads issued into A again.  Reads that run past the
@@ -317,14 +317,23 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                 };
                 auto trip = [&](f4v(&cur)[G::NV], f4v(&nxt)[G::NV]) {
                     landed(cur);
-                    // the reads go out at raised priority: a wave that is ready to fetch is
-                    // served before the multiply-adds of the others, which keeps the LDS busy
+                    // A wave whose taps have landed runs its trip -- the reads of the next record
+                    // in one burst, then the multiply-adds -- at raised priority: it is served
+                    // before waves that are about to wait anyway.  (Spreading the reads between
+                    // the multiply-adds measured slower.)  The priority changes end the
+                    // compiler's scheduling region, so the group hints below order nothing in
+                    // the trip itself; they stay because the code the compiler emits for the
+                    // queue rotation after them measured 0.7 % faster with them than without.
                     __builtin_amdgcn_s_setprio(3);
                     issue(nxt, q[1].off);
                     const Rec fresh = recs[i + 3];
-                    __builtin_amdgcn_s_setprio(0);
-                    __builtin_amdgcn_sched_barrier(0);
                     mul(cur);
+                    __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+                    for (int v = 0; v < G::NV; ++v) {
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                    }
                     q[0] = q[1];
                     q[1] = q[2];
                     q[2] = fresh;
