@@ -716,7 +716,7 @@ const Variant *variants(int *count)
     static const Variant table[] = {
         FSCNN_V4P(32, 2, 2, 4, 8, 3, 1, 2),    //  1  wide, few-channel layers (an RGB image is one chunk): 32x4 tiles, 8 waves
         FSCNN_V4P(32, 2, 4, 4, 16, 14, 0, 2),  //  2  28x28, 56x56 with pooling: 16 waves, 4 channels each, large chunks, pipelined
-        FSCNN_V4P(16, 4, 2, 2, 16, 24, 4, 2),  //  3  14x14: 16x8 tiles, 2 channels per wave, 4 records per trip
+        FSCNN_V4P(16, 4, 2, 2, 16, 25, 4, 2),  //  3  14x14: 16x8 tiles, 2 channels per wave, 4 records per trip; 25 channels fill the LDS (512 channels = 21 chunks)
         FSCNN_V4P(32, 2, 4, 2, 16, 7, 1, 2),   //  4  112x112: 2 channels per wave, two groups per CU
         FSCNN_V4P(32, 2, 2, 4, 16, 12, 1, 2),  //  5  224x224: 32x4 tiles, two groups per CU
         FSCNN_V4P(32, 2, 7, 2, 16, 9, 0, 2),   //  6  32x14 tiles: heights 28 and 56 without idle rows, pipelined
