@@ -715,10 +715,10 @@ const Variant *variants(int *count)
 {
     static const Variant table[] = {
         FSCNN_V4P(32, 2, 2, 4, 8, 3, 1, 2),    //  1  wide, few-channel layers (an RGB image is one chunk): 32x4 tiles, 8 waves
-        FSCNN_V4P(32, 2, 4, 4, 16, 14, 0, 2),  //  2  28x28, 56x56 with pooling: 16 waves, 4 channels each, large chunks, pipelined
+        FSCNN_V4P(32, 2, 4, 4, 16, 14, 0, 2),  //  2  32x8 tiles, 16 waves, 4 channels each, large chunks, pipelined (second choice after 6)
         FSCNN_V4P(16, 4, 2, 2, 16, 25, 4, 2),  //  3  14x14: 16x8 tiles, 2 channels per wave, 4 records per trip; 25 channels fill the LDS (512 channels = 21 chunks)
-        FSCNN_V4P(32, 2, 4, 2, 16, 7, 1, 2),   //  4  112x112: 2 channels per wave, two groups per CU
-        FSCNN_V4P(32, 2, 2, 4, 16, 12, 1, 2),  //  5  224x224: 32x4 tiles, two groups per CU
+        FSCNN_V4P(32, 2, 4, 2, 16, 7, 1, 2),   //  4  32x8 tiles, 2 channels per wave, two groups per CU (second choice after 26 on 112x112)
+        FSCNN_V4P(32, 2, 2, 4, 16, 12, 1, 2),  //  5  32x4 tiles, two groups per CU (second choice after 26 on 224x224)
         FSCNN_V4P(32, 2, 7, 2, 16, 9, 0, 2),   //  6  32x14 tiles: heights 28 and 56 without idle rows, pipelined
         FSCNN_V4(64, 1, 4, 4, 16, 8, 1, 3),    //  7  64-wide rows
         FSCNN_V4(16, 1, 4, 4, 8, 4, 1, 3),     //  8  16 images per group
