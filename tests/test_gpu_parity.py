@@ -741,7 +741,9 @@ def test_filter_handle_serves_two_streams_at_once(F):
     wa = host(F.conv2d_sparse_filter(f, xad, (1, 1), (1, 1), bd, True))
     wb = host(F.conv2d_sparse_filter(f, xbd, (1, 1), (1, 1), bd, True))
     for ya, yb in outs:
-        assert np.array_equal(host(ya), wa) and np.array_equal(host(yb), wb)
+        # equal up to the last bits: small problems may run in the channel-split mode, whose
+        # partial sums arrive in no fixed order
+        assert np.allclose(host(ya), wa, rtol=1e-5, atol=1e-6) and np.allclose(host(yb), wb, rtol=1e-5, atol=1e-6)
     o, a = oracle.conv2d_dense(xa, w, (1, 1), (1, 1), b, True, want_abs=True)
     assert_parity(wa, o, a, row_nmax(w), "two streams, first input")
 
