@@ -184,14 +184,13 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
     const int ox0 = ((tg % tiles_x) * G::WX + wave % G::WX) * G::TP;
     const bool patch_live = oy0 < Ho && ox0 < Wo;   // wave-uniform
 
-    // staging: line q of a chunk (1 KiB) holds rows (q*1024 + 16*lane) / ROW_BYTES of the chunk
-    int goff[G::NLW];
-#pragma unroll
-    for (int j = 0; j < G::NLW; ++j) {
-        const int byte = (wave + j * G::WAVES) * 1024 + lane * 16;
-        const int row = byte / G::ROW_BYTES, col = byte % G::ROW_BYTES;
-        goff[j] = (row * Kpad + kt * G::KT) * 4 + col;
-    }
+    // staging: line q of a chunk (1 KiB) holds rows (q*1024 + 16*lane) / ROW_BYTES of the chunk.
+    // A wave fills lines wave, wave + WAVES, ...: their global offsets are goff0 + j * gstep (one
+    // register instead of a table: the pixel loop below leaves none to spare).
+    static_assert(1024 % G::ROW_BYTES == 0, "a line holds whole rows");
+    const int byte0 = wave * 1024 + lane * 16;
+    const int goff0 = ((byte0 / G::ROW_BYTES) * Kpad + kt * G::KT) * 4 + byte0 % G::ROW_BYTES;
+    const int gstep = G::WAVES * (1024 / G::ROW_BYTES) * Kpad * 4;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ldsb;
     const long long wbytes = (long long)C * G::RS * Kpad * 4;
     auto fetch = [&](int ci, int buf) {
@@ -200,23 +199,31 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
         const long long left = wbytes - first;   // rows past the last channel read as zero
         const int4v rs = {(int)(uint32_t)base, (int)((base >> 32) & 0xffffu),
                           (int)(left > 0x7fffffffLL ? 0x7fffffffLL : left), 0x00020000};
+        int off = goff0;
 #pragma unroll
         for (int j = 0; j < G::NLW; ++j) {
             const int line = wave + j * G::WAVES;
+            // recomputed at every use: hoisted out of the chunk loop the offsets would occupy
+            // NLW registers again (and be spilled)
+            asm volatile("" : "+v"(off));
             if (line < G::NLINE)
-                lds_dma_dwordx4(rs, lds0 + (uint32_t)(buf * G::BUF_BYTES + line * 1024), goff[j]);
+                lds_dma_dwordx4(rs, lds0 + (uint32_t)(buf * G::BUF_BYTES + line * 1024), off);
+            off += gstep;
         }
     };
 
     // Lanes 0..35 stand for the 6x6 input pixels of patch + halo.  Per chunk, each of these lanes
-    // loads its pixel's list bounds (two chunks ahead) and the first EV (channel, value) pairs
+    // loads where its pixel's list continues (three chunks ahead) and the first EV (channel, value) pairs
     // of the list (one chunk ahead) with vector loads, so that no latency is left when the wave
     // walks the pixels: it picks bounds and pairs out of the registers with readlane.
     const int pa = lane / G::HP, pb = lane % G::HP;
     const int piy = oy0 - ph + pa, pix_ = ox0 - pw + pb;
     const bool pin_img = patch_live && lane < G::NPIX && piy >= 0 && piy < H && pix_ >= 0 && pix_ < W;
     // a lane without a pixel reads the bounds of the image's first pixel and is masked afterwards
-    const int *cp = cptr + (((long long)n * H + (pin_img ? piy : 0)) * W + (pin_img ? pix_ : 0)) * NCP;
+    // kept as a 32-bit element offset into the image's part of the pointer array (the whole
+    // array has fewer than 2^31 entries) and widened at each use: one register less to hold
+    const int *cimg = cptr + (long long)n * H * W * NCP;
+    const int cpo = ((pin_img ? piy : 0) * W + (pin_img ? pix_ : 0)) * NCP;
     // These loads are inline assembly like the staging loads, and for the same reason: the
     // compiler cannot count the direct-to-LDS loads, so any vector load it does know makes it
     // wait on vmcnt in the middle of the chunk for loads issued long before, and with them for
@@ -227,12 +234,9 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
         asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p) : "memory");
         return r;
     };
-    auto load_ptrs = [&](int ci, int &beg, int &end) {   // ci may be past the last chunk: empty list
-        const int lo = ci * G::CM < NCP ? ci * G::CM : NCP;
-        const int hi = (ci + 1) * G::CM < NCP ? (ci + 1) * G::CM : NCP;
-        beg = vload(cp + lo);
-        end = vload(cp + hi);
-    };
+    // Position of the first pair of chunk ci in the pixel's list; a chunk ends where the next one
+    // begins, so one value per chunk is enough (ci may be past the last chunk: the list's end).
+    auto load_beg = [&](int ci) { return vload(cimg + (cpo + (ci * G::CM < NCP ? ci * G::CM : NCP))); };
     auto load_pairs = [&](int beg, int (&ec)[G::EV], int (&ev)[G::EV]) {
 #pragma unroll
         for (int e = 0; e < G::EV; ++e) {   // past the list's end: unused values (spare entries)
@@ -241,8 +245,8 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
         }
     };
     // vmcnt(0) that also names every register the loads above fill, so that their uses stay below it
-    auto landed = [&](int &b0, int &e0, int (&c)[G::EV], int (&v)[G::EV]) {
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(b0), "+v"(e0) : : "memory");
+    auto landed = [&](int &b, int (&c)[G::EV], int (&v)[G::EV]) {
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(b) : : "memory");
 #pragma unroll
         for (int e = 0; e < G::EV; ++e) asm volatile("" : "+v"(c[e]), "+v"(v[e]));
     };
@@ -255,22 +259,23 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
 #pragma unroll
             for (int q = 0; q < G::KQ; ++q) acc[a][b][q] = 0.0f;
 
-    int vbeg, vend, nbeg, nend, fbeg, fend;   // bounds of chunks ci, ci+1, ci+2
+    int b0, b1, b2, b3;   // list positions where chunks ci, ci+1, ci+2, ci+3 begin
     int ec[G::EV], nec[G::EV], ev[G::EV], nev[G::EV];   // pairs of chunks ci, ci+1 (values as bit patterns)
     fetch(0, 0);
-    load_ptrs(0, vbeg, vend);
-    load_ptrs(1, nbeg, nend);
-    asm volatile("s_waitcnt vmcnt(0)" : "+v"(vbeg), "+v"(vend), "+v"(nbeg), "+v"(nend) : : "memory");
-    if (!pin_img) vbeg = vend = nbeg = nend = 0;
-    load_pairs(vbeg, ec, ev);
-    landed(vbeg, vend, ec, ev);
+    b0 = load_beg(0);
+    b1 = load_beg(1);
+    b2 = load_beg(2);
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(b0), "+v"(b1), "+v"(b2) : : "memory");
+    if (!pin_img) b0 = b1 = b2 = 0;
+    load_pairs(b0, ec, ev);
+    landed(b0, ec, ev);
     __syncthreads();
 
     for (int ci = 0; ci < NCH; ++ci) {
         const int buf = ci & 1;
         if (ci + 1 < NCH) fetch(ci + 1, buf ^ 1);
-        load_ptrs(ci + 2, fbeg, fend);
-        load_pairs(nbeg, nec, nev);
+        b3 = load_beg(ci + 3);
+        load_pairs(b1, nec, nev);
         const char *wl0 = ldsb + buf * G::BUF_BYTES + lane * (G::KQ * 4);
         if (patch_live) {
 #pragma unroll
@@ -278,8 +283,8 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
 #pragma unroll
             for (int b = 0; b < G::HP; ++b) {
                 const int j = a * G::HP + b;
-                const int beg = __builtin_amdgcn_readlane(vbeg, j);
-                const int cnt = __builtin_amdgcn_readlane(vend, j) - beg;
+                const int beg = __builtin_amdgcn_readlane(b0, j);
+                const int cnt = __builtin_amdgcn_readlane(b1, j) - beg;
                 // one stored (channel, value) pair of input pixel (a, b): read the weight vectors
                 // of every tap the pixel feeds, then multiply
                 auto entry = [&](int c, float v) {
@@ -319,10 +324,9 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
                 }
             }
         }
-        landed(fbeg, fend, nec, nev);   // so have the next chunk's weights
-        if (!pin_img) fbeg = fend = 0;
-        vbeg = nbeg; vend = nend;
-        nbeg = fbeg; nend = fend;
+        landed(b3, nec, nev);   // so have the next chunk's weights
+        if (!pin_img) b3 = 0;
+        b0 = b1; b1 = b2; b2 = b3;
 #pragma unroll
         for (int e = 0; e < G::EV; ++e) {
             ec[e] = nec[e];

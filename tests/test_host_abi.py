@@ -114,3 +114,21 @@ def test_binding_refuses_cpu_tensors():
         fscnn.filter_compress(torch.zeros(2, 2, 3, 3))
     with pytest.raises(TypeError):
         fscnn.input_compress(torch.zeros(1, 2, 3, 3))
+
+
+def test_build_refuses_scratch_in_kernels_with_asynchronous_asm_loads():
+    """The sparse-input kernel's inline-assembly loads fill registers long after they are issued; a
+    register spilled in between would be saved before it is filled, so the build checks the
+    compiler's resource report and fails if such a kernel uses scratch."""
+    from paper_2212_08815_amd import build
+    report = "\n".join([
+        "x.hip:1:1: remark: Function Name: _ZN5fscnn17conv_si_kq_kernelINS_7SiKqCfgILi4ELi4ELi4ELi1EEEEEvPKi [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:1:1: remark:     VGPRs: 128 [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:1:1: remark:     ScratchSize [bytes/lane]: 28 [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:2:1: remark: Function Name: _ZN5fscnn20conv_sf_tiled_kernelIS0_EEvPKf [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:2:1: remark:     ScratchSize [bytes/lane]: 64 [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:3:1: remark: Function Name: _ZN5fscnn17conv_si_kq_kernelINS_7SiKqCfgILi2ELi4ELi2ELi1EEEEEvPKi [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:3:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]",
+    ])
+    bad = build._scratch_users(report)
+    assert len(bad) == 1 and "Li4ELi4ELi4ELi1E" in bad[0] and "28 bytes/lane" in bad[0]
