@@ -145,7 +145,7 @@ fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int
     // N4 tensors need four images per lane whatever the batch size; the choice goes by the
     // output's extent (about the input's divided by the stride)
     int v = tiled_ok ? sf_choose_variant(n4 && N < 4 ? 4 : N, f->C, f->K, (H + sh - 1) / sh, (W + sw - 1) / sw,
-                                         f->R, f->S, sh, pool)
+                                         f->R, f->S, sh, pool, n4)
                      : 0;
     *resolved = v > 0 ? v : -1;
     return FSCNN_OK;

@@ -809,7 +809,7 @@ static long long sf_blocks(const SfGeom &g, int N, int K, int Ho, int Wo)
 // 16x8 tiles with two channels per wave for 14x14, which keeps 256 groups of 16 waves in flight.  A configuration that
 // would launch too few work-groups to cover the 256 compute units, or that has no pooled form
 // when one is asked for, yields to the next one.
-int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool)
+int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool, bool n4)
 {
     int n;
     const Variant *t = variants(&n);
@@ -845,6 +845,9 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int strid
         else if (W > 16) { pref[0] = 12; pref[1] = 13; pref[2] = 13; pref[3] = 13; }
         else { pref[0] = 13; pref[1] = 13; pref[2] = 13; pref[3] = 13; }
     }
+    // NCHW tensors on both sides: staging costs four times the load instructions, so the form
+    // that stages the input half as often (64 channels per group) comes first
+    if (!n4 && pref[0] == 6) { pref[0] = 2; pref[1] = 6; pref[2] = 4; pref[3] = 3; }
     // the 14-row tiles do not pay where they waste more rows than the 8-row ones
     auto covered = [&](const SfGeom &g) {
         return (long long)((W + g.TW - 1) / g.TW) * g.TW * ((H + g.TH - 1) / g.TH) * g.TH;

@@ -150,7 +150,7 @@ int sf_variant_count();
 const char *sf_variant_name(int variant);
 // false if the variant cannot serve RxS filters at this stride
 bool sf_variant_geom(int variant, int R, int S, int sh, int sw, SfGeom *g);
-int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool);
+int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool, bool n4);
 bool sf_variant_has_layout(int variant, int in4, int out4, int pool);
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
