@@ -848,6 +848,8 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int strid
     // NCHW tensors on both sides: staging costs four times the load instructions, so the form
     // that stages the input half as often (64 channels per group) comes first
     if (!n4 && pref[0] == 6) { pref[0] = 2; pref[1] = 6; pref[2] = 4; pref[3] = 3; }
+    // ... and on the wide layers the 32x4 tiles, whose staging lines are the longest runs of x
+    if (!n4 && pref[0] == 26) { pref[3] = pref[2]; pref[2] = pref[1] == 5 ? 4 : pref[1]; pref[1] = 26; pref[0] = 5; }
     // the 14-row tiles do not pay where they waste more rows than the 8-row ones
     auto covered = [&](const SfGeom &g) {
         return (long long)((W + g.TW - 1) / g.TW) * g.TW * ((H + g.TH - 1) / g.TH) * g.TH;
