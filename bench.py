@@ -93,6 +93,67 @@ def run_step(fscnn, x, dev_layers, n, events=None):
     return cur
 
 
+def n4_flat(np, flat, n, k, h, w):
+    """Positions, in an N4 tensor ([ceil(N/4)][K][H][W][4]), of the elements whose NCHW flat indices are `flat`."""
+    ox = flat % w
+    oy = (flat // w) % h
+    kk = (flat // (w * h)) % k
+    nn = flat // (w * h * k)
+    return ((((nn // 4) * k + kk) * h + oy) * w + ox) * 4 + nn % 4
+
+
+def to_host_nchw(fscnn, t, layout, n):
+    """A tensor of the chain as a host N x C x H x W array (plumbing of the check, not of the path)."""
+    if layout == fscnn.N4:
+        t = t.permute(0, 4, 1, 2, 3).reshape(-1, t.shape[1], t.shape[2], t.shape[3])[:n]
+    return t.contiguous().cpu().numpy()
+
+
+def chain_samples(fscnn, torch, np, oracle, x, dev_layers, n, npts=4000, seed=4):
+    """Checks the tensors the last run_step() left behind, layer by layer, against the oracle.
+
+    For every layer yields (li, g, o, a, nmax): g = the launch's stored outputs at npts sampled
+    positions plus the corners of the tensor, o = the oracle's values there computed from the
+    GPU's own previous tensor (so errors do not compound), a = the oracle's sum |w||x| + |b| at
+    those positions, nmax = longest filter row.  Where the 2x2 max-pool is merged into the
+    launch, the oracle value is the maximum of the definition over the pooled window (bias and
+    ReLU applied first, as the separate layers would)."""
+    rng = np.random.default_rng(seed)
+    cur, cur_layout = x, fscnn.NCHW
+    for li, d in enumerate(dev_layers):
+        xin = to_host_nchw(fscnn, cur, cur_layout, n)
+        w = d["w"].cpu().numpy()
+        b = d["bias"].cpu().numpy()
+        k, hw = d["k"], d["hw"]
+        oh = hw // 2 if d["fused"] else hw
+        total = n * k * oh * oh
+        flat = rng.choice(total, size=min(npts, total), replace=False)
+        flat = np.unique(np.concatenate([flat, [0, oh - 1, total - 1, total - oh]])).astype(np.int64)
+        y = d["y"]
+        pos = n4_flat(np, flat, n, k, oh, oh) if d["lay_out"] == fscnn.N4 else flat
+        g = y.view(-1)[torch.from_numpy(pos).cuda()].cpu().numpy()
+        if d["fused"]:
+            px, py = flat % oh, (flat // oh) % oh
+            nk = flat // (oh * oh)
+            win = np.stack([(nk * hw + 2 * py + dy) * hw + 2 * px + dx for dy in (0, 1) for dx in (0, 1)], 1)
+            o4, a4 = oracle.conv2d_points(xin, w, win.ravel(), (1, 1), (1, 1), b, d["relu"], want_abs=True)
+            o, a = o4.reshape(-1, 4).max(1), a4.reshape(-1, 4).max(1)
+        else:
+            o, a = oracle.conv2d_points(xin, w, flat, (1, 1), (1, 1), b, d["relu"], want_abs=True)
+        nmax = int(np.count_nonzero(w.reshape(k, -1), axis=1).max())
+        yield li, g, o, a, nmax
+        cur, cur_layout = y, d["lay_out"]
+        if d["pool"] and not d["fused"]:
+            cur = d["p"]
+
+
+def rel_err(np, g, o):
+    """max |g - o| / max(|o|, rms(o)): the comparison rule of the parity tests."""
+    g, o = g.astype(np.float64), o.astype(np.float64)
+    tau = float(np.sqrt(np.mean(o * o)))
+    return float(np.max(np.abs(g - o) / np.maximum(np.abs(o), tau if tau > 0 else 1.0)))
+
+
 def time_gpu(torch, fn, iters):
     """Average milliseconds of fn() over `iters` calls (HIP events on the current stream)."""
     fn()
@@ -269,6 +330,9 @@ def main():
     ap.add_argument("--separate-pool", action="store_true",
                     help="run the 4 max-pools as separate helper kernels instead of the merged conv+pool epilogue")
     ap.add_argument("--no-rows", action="store_true", help="skip the measurements outside the timed stack")
+    ap.add_argument("--no-check", action="store_true",
+                    help="skip the comparison of every layer's stored tensor with the CPU oracle on sampled outputs")
+    ap.add_argument("--check-points", type=int, default=4000, help="sampled outputs per layer of that comparison")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="run only a plain copy-like kernel of known size (1 GiB read, 1 GiB written) three "
                          "times; used to scale the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
@@ -318,6 +382,29 @@ def main():
     for _ in range(max(args.warmup, 1)):       # also builds every plan: the timed loop allocates nothing
         run_step(fscnn, x, dev_layers, n)
     torch.cuda.synchronize()
+
+    # The tensors of the very chain that is timed below (same launches, layouts and automatic
+    # configurations), compared with the oracle before the clock starts.
+    check = None
+    if not args.no_check:
+        import oracle
+        errs = []
+        for li, g, o, a, nmax in chain_samples(fscnn, torch, np, oracle, x, dev_layers, n, args.check_points):
+            if not np.all(np.isfinite(g)):
+                errs.append(float("inf"))
+                continue
+            bound = (nmax + 2) * 2.0 ** -24 * 1.01 * a + 2.0 ** -24 * np.abs(o.astype(np.float64)) + 1e-45
+            errs.append((rel_err(np, g, o), float(np.max(np.abs(g.astype(np.float64) - o) / bound))))
+        worst = max(e[0] if isinstance(e, tuple) else e for e in errs)
+        check = dict(max_rel_err=worst, tolerance=1e-4, passed=bool(worst <= 1e-4),
+                     per_layer_rel_err=[e[0] if isinstance(e, tuple) else e for e in errs],
+                     per_layer_share_of_fp32_summation_bound=[e[1] if isinstance(e, tuple) else None for e in errs],
+                     points_per_layer=args.check_points,
+                     rule="|g-o| / max(|o|, rms(o)) over sampled outputs + tensor corners of every layer, oracle fed "
+                          "the GPU's previous tensor; pooled launches against the max of the definition over the window")
+        if not check["passed"]:
+            print("bench.py: the timed chain does NOT match the oracle: %r" % (check,), file=sys.stderr)
+            sys.exit(3)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     if args.separate_pool:
@@ -404,6 +491,8 @@ def main():
                                / (layer_ms[i] * 1e-3), 3) for i in range(len(layer_ms))],
         filter_compress_ms_all_layers=compress_ms,
         roofline=roofline,
+        max_rel_err=None if check is None else check["max_rel_err"],
+        check=check,
     )
     if not args.no_rows:
         out["other_rows"] = other_rows(fscnn, torch, inputs, np, dev_layers)
