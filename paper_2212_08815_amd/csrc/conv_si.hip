@@ -213,9 +213,9 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
     };
 
     // Lanes 0..35 stand for the 6x6 input pixels of patch + halo.  Per chunk, each of these lanes
-    // loads where its pixel's list continues (three chunks ahead) and the first EV (channel, value) pairs
-    // of the list (one chunk ahead) with vector loads, so that no latency is left when the wave
-    // walks the pixels: it picks bounds and pairs out of the registers with readlane.
+    // loads where its pixel's list continues (three chunks ahead) and the first EV (channel, value)
+    // pairs of the list (one chunk ahead) with vector loads; when the wave walks the pixels it
+    // picks bounds and pairs out of the registers with readlane.
     const int pa = lane / G::HP, pb = lane % G::HP;
     const int piy = oy0 - ph + pa, pix_ = ox0 - pw + pb;
     const bool pin_img = patch_live && lane < G::NPIX && piy >= 0 && piy < H && pix_ >= 0 && pix_ < W;
@@ -224,32 +224,52 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
     // array has fewer than 2^31 entries) and widened at each use: one register less to hold
     const int *cimg = cptr + (long long)n * H * W * NCP;
     const int cpo = ((pin_img ? piy : 0) * W + (pin_img ? pix_ : 0)) * NCP;
-    // These loads are inline assembly like the staging loads, and for the same reason: the
-    // compiler cannot count the direct-to-LDS loads, so any vector load it does know makes it
-    // wait on vmcnt in the middle of the chunk for loads issued long before, and with them for
-    // the weights that should arrive in the background.  Nothing reads the results before the
-    // wait at the end of the chunk (landed(), which names them).
-    auto vload = [&](const void *p) {
-        int r;
-        asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p) : "memory");
-        return r;
+    // The list positions and the first EV pairs of the NEXT chunk are fetched by ONE inline
+    // assembly statement that issues the loads AND waits for them (s_waitcnt vmcnt(0)) before it
+    // ends: its outputs are complete when the compiler first sees them, so no register is ever
+    // "in flight" from the compiler's point of view and it may copy, split or spill them as it
+    // likes.  (Loads the compiler itself knows are not an option here: it cannot count the
+    // direct-to-LDS loads of the weights, and its own vmcnt waits in front of every use of a
+    // loaded register would then also wait for weights that should arrive in the background.)
+    // The statement sits in the middle of the pixel walk: the wave that executes it waits for one
+    // memory round trip there, while the other waves of the SIMD, which are at other points of
+    // their walks, keep the vector ALUs and the LDS busy.  The vmcnt(0) also covers this wave's
+    // staging loads of the next chunk, issued at the top of the chunk.
+    typedef int i4v __attribute__((ext_vector_type(4)));
+    typedef int i2v __attribute__((ext_vector_type(2)));
+    static_assert(G::EV == 4 || G::EV == 6, "pairs are fetched as one 16-byte vector, or one of 16 and one of 8 bytes");
+    auto load_chunk = [&](const int *pb, int beg, int &b, int (&c)[G::EV], int (&v)[G::EV]) {
+        const uint32_t *pc = cidx + beg;
+        const float *pv = xval + beg;
+        i4v c4, v4;
+        if constexpr (G::EV == 4) {
+            asm volatile("global_load_dword %0, %3, off\n\t"
+                         "global_load_dwordx4 %1, %4, off\n\t"
+                         "global_load_dwordx4 %2, %5, off\n\t"
+                         "s_waitcnt vmcnt(0)"
+                         : "=&v"(b), "=&v"(c4), "=&v"(v4)
+                         : "v"(pb), "v"(pc), "v"(pv)
+                         : "memory");
+        } else {
+            i2v c2, v2;
+            asm volatile("global_load_dword %0, %5, off\n\t"
+                         "global_load_dwordx4 %1, %6, off\n\t"
+                         "global_load_dwordx2 %2, %6, off offset:16\n\t"
+                         "global_load_dwordx4 %3, %7, off\n\t"
+                         "global_load_dwordx2 %4, %7, off offset:16\n\t"
+                         "s_waitcnt vmcnt(0)"
+                         : "=&v"(b), "=&v"(c4), "=&v"(c2), "=&v"(v4), "=&v"(v2)
+                         : "v"(pb), "v"(pc), "v"(pv)
+                         : "memory");
+            c[4] = c2.x; c[5] = c2.y;
+            v[4] = v2.x; v[5] = v2.y;
+        }
+        c[0] = c4.x; c[1] = c4.y; c[2] = c4.z; c[3] = c4.w;
+        v[0] = v4.x; v[1] = v4.y; v[2] = v4.z; v[3] = v4.w;
     };
     // Position of the first pair of chunk ci in the pixel's list; a chunk ends where the next one
     // begins, so one value per chunk is enough (ci may be past the last chunk: the list's end).
-    auto load_beg = [&](int ci) { return vload(cimg + (cpo + (ci * G::CM < NCP ? ci * G::CM : NCP))); };
-    auto load_pairs = [&](int beg, int (&ec)[G::EV], int (&ev)[G::EV]) {
-#pragma unroll
-        for (int e = 0; e < G::EV; ++e) {   // past the list's end: unused values (spare entries)
-            ec[e] = vload(cidx + beg + e);
-            ev[e] = vload(xval + beg + e);
-        }
-    };
-    // vmcnt(0) that also names every register the loads above fill, so that their uses stay below it
-    auto landed = [&](int &b, int (&c)[G::EV], int (&v)[G::EV]) {
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(b) : : "memory");
-#pragma unroll
-        for (int e = 0; e < G::EV; ++e) asm volatile("" : "+v"(c[e]), "+v"(v[e]));
-    };
+    auto beg_ptr = [&](int ci) { return cimg + (cpo + (ci * G::CM < NCP ? ci * G::CM : NCP)); };
 
     float acc[G::TP][G::TP][G::KQ];
 #pragma unroll
@@ -259,29 +279,31 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
 #pragma unroll
             for (int q = 0; q < G::KQ; ++q) acc[a][b][q] = 0.0f;
 
-    int b0, b1, b2, b3;   // list positions where chunks ci, ci+1, ci+2, ci+3 begin
+    int b0, b1, b2;       // list positions where chunks ci, ci+1, ci+2 begin
     int ec[G::EV], nec[G::EV], ev[G::EV], nev[G::EV];   // pairs of chunks ci, ci+1 (values as bit patterns)
+#pragma unroll
+    for (int e = 0; e < G::EV; ++e) nec[e] = nev[e] = 0;
     fetch(0, 0);
-    b0 = load_beg(0);
-    b1 = load_beg(1);
-    b2 = load_beg(2);
-    asm volatile("s_waitcnt vmcnt(0)" : "+v"(b0), "+v"(b1), "+v"(b2) : : "memory");
-    if (!pin_img) b0 = b1 = b2 = 0;
-    load_pairs(b0, ec, ev);
-    landed(b0, ec, ev);
+    b0 = *beg_ptr(0);
+    b1 = *beg_ptr(1);
+    if (!pin_img) b0 = b1 = 0;
+    load_chunk(beg_ptr(2), b0, b2, ec, ev);   // also waits for the staging loads of chunk 0
+    if (!pin_img) b2 = 0;
     __syncthreads();
 
     for (int ci = 0; ci < NCH; ++ci) {
         const int buf = ci & 1;
         if (ci + 1 < NCH) fetch(ci + 1, buf ^ 1);
-        b3 = load_beg(ci + 3);
-        load_pairs(b1, nec, nev);
+        int b3 = 0;
         const char *wl0 = ldsb + buf * G::BUF_BYTES + lane * (G::KQ * 4);
         if (patch_live) {
 #pragma unroll
             for (int a = 0; a < G::HP; ++a)
 #pragma unroll
             for (int b = 0; b < G::HP; ++b) {
+                // half way through the walk: where the list continues three chunks on, and the
+                // first pairs of the next chunk
+                if (a == G::HP / 2 && b == 0) load_chunk(beg_ptr(ci + 3), b1, b3, nec, nev);
                 const int j = a * G::HP + b;
                 const int beg = __builtin_amdgcn_readlane(b0, j);
                 const int cnt = __builtin_amdgcn_readlane(b1, j) - beg;
@@ -324,7 +346,7 @@ conv_si_kq_kernel(const int *__restrict__ cptr, const uint32_t *__restrict__ cid
                 }
             }
         }
-        landed(b3, nec, nev);   // so have the next chunk's weights
+        wait_vmcnt<0>();   // a wave without a patch has not waited for its staging loads yet
         if (!pin_img) b3 = 0;
         b0 = b1; b1 = b2; b2 = b3;
 #pragma unroll
