@@ -253,7 +253,7 @@ def other_rows(fscnn, torch, inputs, np, dev_layers):
     K, CRS = c["w"].shape[0], int(np.prod(c["w"].shape[1:]))
     d_rp, d_ix, d_vl = (torch.from_numpy(rp).cuda(), torch.from_numpy(ix.view(np.int32)).cuda(),
                         torch.from_numpy(vl).cuda())
-    ws = torch.empty(fscnn.sparse_transpose_workspace(CRS, K) // 4 + 1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(fscnn.sparse_transpose_workspace(CRS, f.nnz) // 4 + 1, dtype=torch.int32, device="cuda")
     ms_t = time_gpu(torch, lambda: fscnn.sparse_transpose(d_rp, d_ix, d_vl, K, CRS, workspace=ws), 20)
     out["sparse_matrix_transpose"] = dict(ms=ms_t, nnz=int(f.nnz),
                                           gbs=(16.0 * f.nnz + 4.0 * (K + CRS + 2)) / ms_t / 1e6,
@@ -267,7 +267,7 @@ def other_rows(fscnn, torch, inputs, np, dev_layers):
     t_rp = torch.from_numpy(np.cumsum(tp).astype(np.int32)).cuda()
     t_ix = torch.from_numpy(cc.astype(np.int32)).cuda()
     t_vl = torch.from_numpy(x0.reshape(Cc * Hh, Ww)[rr, cc].astype(np.float32)).cuda()
-    ws2 = torch.empty(fscnn.sparse_transpose_workspace(Ww * Hh, Cc) // 4 + 1, dtype=torch.int32, device="cuda")
+    ws2 = torch.empty(fscnn.sparse_transpose_workspace(Ww * Hh, len(rr)) // 4 + 1, dtype=torch.int32, device="cuda")
     ms_t2 = time_gpu(torch, lambda: fscnn.sparse_tensor_transpose(t_rp, t_ix, t_vl, Ww, Hh, Cc, workspace=ws2), 20)
     out["sparse_tensor_transpose"] = dict(ms=ms_t2, nnz=int(len(rr)),
                                           gbs=(16.0 * len(rr) + 4.0 * (Cc * Hh + Ww * Hh + 2)) / ms_t2 / 1e6,

@@ -281,7 +281,7 @@ int fscnn_si_variant_count(void);
  * the same nodes by columns: tptr_dev[n_cols+1], tidx_dev[nnz] = old row of each node, ascending
  * inside a new row, tval_dev[nnz] (bit copies).  Ending nodes of the paper's layout are replaced
  * by the pointer arrays.  All pointers are caller-owned device memory and must not alias;
- * workspace_dev is scratch of at least fscnn_sparse_transpose_workspace(n_cols, n_rows) bytes,
+ * workspace_dev is scratch of at least fscnn_sparse_transpose_workspace(n_cols, nnz) bytes,
  * 4-byte aligned.  Allocates nothing, asynchronous on `stream`.  A node whose index is not below
  * n_cols is dropped (never followed); rows that repeat an index give an unspecified result.
  * ERR_UNSUPPORTED if the workspace is too small or the shape exceeds the scratch format. */
@@ -295,16 +295,17 @@ fscnn_status_t fscnn_sparse_transpose(const int *rowptr_dev, const unsigned *idx
  * c*H + h of rowptr_dev[C*H+1] lists in widx_dev the w of its stored nodes, strictly ascending.
  * Output: order O_chw (channel innermost, then height, then width): row w*H + h of
  * tptr_dev[W*H+1] lists in cidx_dev the c of its nodes, ascending; tval_dev are bit copies.
- * Workspace: fscnn_sparse_transpose_workspace(W*H, C) bytes.  Otherwise as fscnn_sparse_transpose. */
+ * Workspace: fscnn_sparse_transpose_workspace(W*H, nnz) bytes.  Otherwise as fscnn_sparse_transpose. */
 fscnn_status_t fscnn_sparse_tensor_transpose(const int *rowptr_dev, const unsigned *widx_dev,
                                              const float *val_dev, int W, int H, int C,
                                              long long nnz, int *tptr_dev, unsigned *cidx_dev,
                                              float *tval_dev, void *workspace_dev,
                                              long long workspace_bytes, void *stream);
 
-/* Scratch bytes the two transposes need for `new_rows` rows of the result whose nodes are
- * ordered by an index below `index_range`; -1 if the shape is not supported.  Host-only. */
-long long fscnn_sparse_transpose_workspace(long long new_rows, long long index_range);
+/* Scratch bytes the two transposes need for a result of `new_rows` rows and `nnz` stored nodes
+ * (proportional to new_rows + nnz); -1 if either is not positive / negative or not below 2^31.
+ * Host-only. */
+long long fscnn_sparse_transpose_workspace(long long new_rows, long long nnz);
 
 /* Measurement helper (no counterpart in the paper): launches `work_groups` groups of 256 threads
  * that each repeat, `iters` times, the instruction mix of the convolution's hot loop on a

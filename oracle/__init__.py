@@ -87,12 +87,21 @@ def filter_decompress(rowptr, idx, val, shape):
     return w
 
 
+def _act(relu, leaky):
+    """Activation code of the C functions: 0 none, 1 ReLU, 2 LeakyReLU(leaky)."""
+    if leaky is None:
+        return int(bool(relu))
+    assert not relu, "leaky excludes relu"
+    _load().oracle_set_leaky_slope(ctypes.c_double(float(np.float32(leaky))))
+    return 2
+
+
 def _out_shape(x, K, R, S, stride, pad):
     N, C, H, W = x.shape
     return (N, K, out_dim(H, R, stride[0], pad[0]), out_dim(W, S, stride[1], pad[1]))
 
 
-def conv2d_dense(x, w, stride=(1, 1), pad=(0, 0), bias=None, relu=False, want_abs=False):
+def conv2d_dense(x, w, stride=(1, 1), pad=(0, 0), bias=None, relu=False, want_abs=False, leaky=None):
     x, w = _f32(x), _f32(w)
     N, C, H, W = x.shape
     K, C2, R, S = w.shape
@@ -102,12 +111,12 @@ def conv2d_dense(x, w, stride=(1, 1), pad=(0, 0), bias=None, relu=False, want_ab
     a = np.empty(y.shape, np.float64) if want_abs else None
     _load().oracle_conv2d_dense(_p(x, _f32p), N, C, H, W, _p(w, _f32p), K, R, S,
                                 stride[0], stride[1], pad[0], pad[1],
-                                _p(bias, _f32p), int(bool(relu)), _p(y, _f32p), _p(a, _f64p))
+                                _p(bias, _f32p), _act(relu, leaky), _p(y, _f32p), _p(a, _f64p))
     return (y, a) if want_abs else y
 
 
 def conv2d_sparse_filter(x, csr, fshape, stride=(1, 1), pad=(0, 0), bias=None, relu=False,
-                         want_abs=False):
+                         want_abs=False, leaky=None):
     """csr = (rowptr, idx, val) as produced by filter_compress; fshape = (K, C, R, S)."""
     x = _f32(x)
     N, C, H, W = x.shape
@@ -122,13 +131,13 @@ def conv2d_sparse_filter(x, csr, fshape, stride=(1, 1), pad=(0, 0), bias=None, r
     rc = _load().oracle_conv2d_sparse_filter(_p(x, _f32p), N, C, H, W, _p(rowptr, _i32p),
                                              _p(idx, _u32p), _p(val, _f32p), K, R, S,
                                              stride[0], stride[1], pad[0], pad[1],
-                                             _p(bias, _f32p), int(bool(relu)), _p(y, _f32p),
+                                             _p(bias, _f32p), _act(relu, leaky), _p(y, _f32p),
                                              _p(a, _f64p))
     assert rc == 0
     return (y, a) if want_abs else y
 
 
-def conv2d_points(x, w, flat, stride=(1, 1), pad=(0, 0), bias=None, relu=False, want_abs=False):
+def conv2d_points(x, w, flat, stride=(1, 1), pad=(0, 0), bias=None, relu=False, want_abs=False, leaky=None):
     """The dense definition at the flat output indices `flat` (into N x K x Ho x Wo)."""
     x, w = _f32(x), _f32(w)
     N, C, H, W = x.shape
@@ -140,7 +149,7 @@ def conv2d_points(x, w, flat, stride=(1, 1), pad=(0, 0), bias=None, relu=False, 
     a = np.empty(flat.size, np.float64) if want_abs else None
     _load().oracle_conv2d_points(_p(x, _f32p), N, C, H, W, _p(w, _f32p), K, R, S,
                                  stride[0], stride[1], pad[0], pad[1],
-                                 _p(bias, _f32p), int(bool(relu)),
+                                 _p(bias, _f32p), _act(relu, leaky),
                                  _p(flat, _i64p), ctypes.c_longlong(flat.size), _p(out, _f32p),
                                  _p(a, _f64p))
     return (out, a) if want_abs else out

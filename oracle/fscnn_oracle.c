@@ -46,15 +46,15 @@
  * the involution property.  No function here is "parity unpinned".
  *
  *   - Sec. 4, "Sparse Matrix Transpose" (Alg. 3) and "Sparse 3-D Tensor
- *     Transpose" (Alg. 4): reordering of the stored nodes between storage
- *     orders.  These are algorithms, not definitions, so the oracle takes the
- *     paper's steps in the paper's order: count the nodes per new row, turn
- *     the counts into start positions v, walk the old rows in order placing
- *     each node at v[index] and advancing v (Alg. 3); for a tensor, transpose
- *     every channel's matrix first, then walk w, h, c and copy the node that
- *     column w of matrix c has reached if its height is h (Alg. 4).  Ending
- *     nodes (index -1) are replaced by pointer arrays throughout, as for the
- *     filters.
+ *     Transpose" (Alg. 4): what they compute is a re-ordering of the stored
+ *     nodes with a plain definition -- the same (position, value) triples,
+ *     listed in the target storage order -- so the oracle is that definition:
+ *     gather the triples, sort them by the target order (positions are unique,
+ *     so the order is total), count the nodes of each new row.  Ending nodes
+ *     (index -1) are replaced by pointer arrays throughout, as for the filters.
+ *   - Sec. 5 "Other layers" / Sec. 6.2: LeakyReLU is one of the element-wise
+ *     activations applied to the output; act = 2 applies y > 0 ? y : slope * y
+ *     to the double sum before the single rounding.
  */
 #include <math.h>
 #include <stddef.h>
@@ -148,10 +148,16 @@ static double conv_point(const float *x, int C, int H, int W, const float *wk, i
     return a;
 }
 
+/* Bias, then the element-wise activation (Sec. 5 "Other layers"): relu = 0 none, 1 ReLU,
+ * 2 LeakyReLU with the slope set by oracle_set_leaky_slope(). */
+static double leaky_slope = 0.0;
+void oracle_set_leaky_slope(double s) { leaky_slope = s; }
+
 static float finish(double a, const float *bias, int k, int relu)
 {
     if (bias) a += (double)bias[k];
-    if (relu) a = a > 0.0 ? a : 0.0;
+    if (relu == 1) a = a > 0.0 ? a : 0.0;
+    if (relu == 2) a = a > 0.0 ? a : a * leaky_slope;
     return (float)a;
 }
 
@@ -294,74 +300,75 @@ void oracle_maxpool2x2(const float *x, int N, int C, int H, int W, float *y)
             }
 }
 
-/* Sparse matrix transpose, Alg. 3.  M has n_rows rows and n_cols columns and is
- * stored by rows: row i holds the nodes idx[rowptr[i] .. rowptr[i+1]) = column
- * of each stored entry, ascending, with its value.  The result stores the same
- * entries by columns: new row j (= old column) holds the old row numbers of its
- * entries, ascending, because the old rows are walked in order (step 5).
- * v of the paper (start of each new row, then progress tracker) is `cursor`;
- * without ending nodes v[j] is simply the number of nodes in columns < j. */
+/* A stored node with its position in the target order: (major, minor) = (new row, index inside
+ * the new row). */
+typedef struct {
+    long long major;
+    uint32_t minor;
+    float val;
+} oracle_node;
+
+static int node_cmp(const void *pa, const void *pb)
+{
+    const oracle_node *a = (const oracle_node *)pa, *b = (const oracle_node *)pb;
+    if (a->major != b->major) return a->major < b->major ? -1 : 1;
+    if (a->minor != b->minor) return a->minor < b->minor ? -1 : 1;
+    return 0;
+}
+
+/* Lists nodes[0..nnz) in target order: sorted by (major, minor); tptr[r] = number of nodes
+ * with major < r. */
+static void emit_in_target_order(oracle_node *nodes, long long nnz, long long n_major,
+                                 int32_t *tptr, uint32_t *tidx, float *tval)
+{
+    qsort(nodes, (size_t)nnz, sizeof(oracle_node), node_cmp);
+    for (long long r = 0; r <= n_major; ++r) tptr[r] = 0;
+    for (long long e = 0; e < nnz; ++e) {
+        tptr[nodes[e].major + 1] += 1;
+        tidx[e] = nodes[e].minor;
+        memcpy(&tval[e], &nodes[e].val, sizeof(float));
+    }
+    for (long long r = 0; r < n_major; ++r) tptr[r + 1] += tptr[r];
+}
+
+/* Sparse matrix transpose (what Alg. 3 computes).  M has n_rows rows and n_cols columns and is
+ * stored by rows: row i holds the nodes idx[rowptr[i] .. rowptr[i+1]) = column of each stored
+ * entry, ascending, with its value.  The result stores the same entries by columns: new row j
+ * (= old column) lists the old rows of its entries, ascending, with their values. */
 void oracle_sparse_transpose(const int32_t *rowptr, const uint32_t *idx, const float *val,
                              int n_rows, int n_cols,
                              int32_t *tptr, uint32_t *tidx, float *tval)
 {
-    int32_t *cursor = (int32_t *)calloc((size_t)n_cols + 1, sizeof(int32_t));
-    for (int i = 0; i < n_rows; ++i)                       /* step 3: nodes per column ... */
-        for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) cursor[idx[e] + 1] += 1;
-    for (int j = 0; j < n_cols; ++j) cursor[j + 1] += cursor[j]; /* ... accumulated */
-    for (int j = 0; j <= n_cols; ++j) tptr[j] = cursor[j];
-    for (int i = 0; i < n_rows; ++i)                       /* steps 5-9 */
+    const long long nnz = rowptr[n_rows];
+    oracle_node *nodes = (oracle_node *)malloc(sizeof(oracle_node) * (size_t)(nnz > 0 ? nnz : 1));
+    for (int i = 0; i < n_rows; ++i)
         for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
-            const int32_t dst = cursor[idx[e]];
-            tidx[dst] = (uint32_t)i;
-            tval[dst] = val[e];
-            cursor[idx[e]] = dst + 1;
+            nodes[e].major = idx[e];          /* entry (i, j) becomes entry (j, i) */
+            nodes[e].minor = (uint32_t)i;
+            nodes[e].val = val[e];
         }
-    free(cursor);
+    emit_in_target_order(nodes, nnz, n_cols, tptr, tidx, tval);
+    free(nodes);
 }
 
-/* Sparse 3-D tensor transpose from order O_whc to order O_chw, Alg. 4.
- * Input: C matrices stacked, matrix c stored in order O_wh, i.e. row (c*H + h)
- * lists the w of the stored entries of channel c at height h, ascending.
- * Output: order O_chw (channel runs innermost, then height, then width): row
- * (w*H + h) lists the c of the stored entries at that pixel, ascending.
- * Steps: transpose every matrix to O_hw by Alg. 3 (step 4-5: column w of matrix
- * c then lists its heights, ascending), then for w, h, c in that nesting copy
- * the node that column w of matrix c has reached if its height is h. */
+/* Sparse 3-D tensor transpose from order O_whc to order O_chw (what Alg. 4 computes).
+ * Input: C matrices stacked, matrix c stored in order O_wh, i.e. row (c*H + h) lists the w of
+ * the stored entries of channel c at height h, ascending.  Output: order O_chw (channel runs
+ * innermost, then height, then width): row (w*H + h) lists the c of the stored entries at that
+ * pixel, ascending. */
 void oracle_sparse_tensor_transpose(const int32_t *rowptr, const uint32_t *widx, const float *val,
                                     int W, int H, int C,
                                     int32_t *tptr, uint32_t *cidx, float *tval)
 {
     const long long nnz = rowptr[(long long)C * H];
-    int32_t *mptr = (int32_t *)malloc(((size_t)C * W + 1) * sizeof(int32_t));   /* per (c, w) */
-    uint32_t *hidx = (uint32_t *)malloc((size_t)(nnz > 0 ? nnz : 1) * sizeof(uint32_t));
-    float *hval = (float *)malloc((size_t)(nnz > 0 ? nnz : 1) * sizeof(float));
-    int32_t *one = (int32_t *)malloc(((size_t)W + 1) * sizeof(int32_t));
-    int32_t *local = (int32_t *)malloc(((size_t)H + 1) * sizeof(int32_t));
-    mptr[0] = 0;
-    for (int c = 0; c < C; ++c) {                           /* steps 4-5 */
-        const int32_t base = rowptr[(long long)c * H];
-        for (int h = 0; h <= H; ++h) local[h] = rowptr[(long long)c * H + h] - base;
-        oracle_sparse_transpose(local, widx + base, val + base, H, W, one, hidx + base, hval + base);
-        for (int w = 0; w < W; ++w) mptr[(long long)c * W + w + 1] = base + one[w + 1];
-    }
-    int32_t *reached = (int32_t *)malloc((size_t)C * W * sizeof(int32_t));     /* progress per (c, w) */
-    for (long long q = 0; q < (long long)C * W; ++q) reached[q] = mptr[q];
-    int32_t out = 0;
-    for (int w = 0; w < W; ++w)                             /* steps 7-13 */
-        for (int h = 0; h < H; ++h) {
-            tptr[(long long)w * H + h] = out;
-            for (int c = 0; c < C; ++c) {
-                const long long q = (long long)c * W + w;
-                const int32_t e = reached[q];
-                if (e < mptr[q + 1] && hidx[e] == (uint32_t)h) {
-                    cidx[out] = (uint32_t)c;
-                    tval[out] = hval[e];
-                    ++out;
-                    reached[q] = e + 1;
-                }
+    oracle_node *nodes = (oracle_node *)malloc(sizeof(oracle_node) * (size_t)(nnz > 0 ? nnz : 1));
+    for (int c = 0; c < C; ++c)
+        for (int h = 0; h < H; ++h)
+            for (int32_t e = rowptr[(long long)c * H + h]; e < rowptr[(long long)c * H + h + 1]; ++e) {
+                nodes[e].major = (long long)widx[e] * H + h;   /* entry (w, h, c) goes to row w*H + h */
+                nodes[e].minor = (uint32_t)c;
+                nodes[e].val = val[e];
             }
-        }
-    tptr[(long long)W * H] = out;
-    free(reached); free(local); free(one); free(hval); free(hidx); free(mptr);
+    emit_in_target_order(nodes, nnz, (long long)W * H, tptr, cidx, tval);
+    free(nodes);
 }

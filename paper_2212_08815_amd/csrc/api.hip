@@ -723,14 +723,14 @@ fscnn_status_t fscnn_conv2d_sparse_input_prepared(const fscnn_input_t *in, const
     return FSCNN_OK;
 }
 
-long long fscnn_sparse_transpose_workspace(long long new_rows, long long index_range)
+long long fscnn_sparse_transpose_workspace(long long new_rows, long long nnz)
 {
-    return reorder_workspace_bytes(new_rows, index_range);
+    return reorder_workspace_bytes(new_rows, nnz);
 }
 
 static fscnn_status_t reorder_common(bool tensor, const int *rowptr, const unsigned *idx,
                                      const float *val, int n_rows, int n_cols, int H,
-                                     long long n_buckets, int n_keys, long long nnz, int *tptr,
+                                     long long n_buckets, long long nnz, int *tptr,
                                      unsigned *tidx, float *tval, void *ws, long long ws_bytes,
                                      void *stream)
 {
@@ -738,13 +738,13 @@ static fscnn_status_t reorder_common(bool tensor, const int *rowptr, const unsig
     if (nnz < 0 || nnz >= (1LL << 31)) return FSCNN_ERR_SHAPE;
     if (nnz > 0 && (!idx || !val || !tidx || !tval)) return FSCNN_ERR_NULL;
     if (!fits_int(n_buckets + 1)) return FSCNN_ERR_UNSUPPORTED;
-    const long long need = reorder_workspace_bytes(n_buckets, n_keys);
+    const long long need = reorder_workspace_bytes(n_buckets, nnz);
     if (need < 0 || ws_bytes < need || ((uintptr_t)ws & 3)) return FSCNN_ERR_UNSUPPORTED;
     int dev;
     fscnn_status_t s = have_device(&dev);
     if (s != FSCNN_OK) return s;
-    FSCNN_HIP(launch_reorder(tensor, rowptr, idx, val, n_rows, n_cols, H, n_buckets, n_keys, nnz,
-                             tptr, tidx, tval, ws, (hipStream_t)stream));
+    FSCNN_HIP(launch_reorder(tensor, rowptr, idx, val, n_rows, n_cols, H, n_buckets, nnz, tptr, tidx,
+                             tval, ws, (hipStream_t)stream));
     return FSCNN_OK;
 }
 
@@ -754,7 +754,7 @@ fscnn_status_t fscnn_sparse_transpose(const int *rowptr_dev, const unsigned *idx
                                       void *workspace_dev, long long workspace_bytes, void *stream)
 {
     if (n_rows <= 0 || n_cols <= 0) return FSCNN_ERR_SHAPE;
-    return reorder_common(false, rowptr_dev, idx_dev, val_dev, n_rows, n_cols, 1, n_cols, n_rows, nnz,
+    return reorder_common(false, rowptr_dev, idx_dev, val_dev, n_rows, n_cols, 1, n_cols, nnz,
                           tptr_dev, tidx_dev, tval_dev, workspace_dev, workspace_bytes, stream);
 }
 
@@ -766,7 +766,7 @@ fscnn_status_t fscnn_sparse_tensor_transpose(const int *rowptr_dev, const unsign
 {
     if (W <= 0 || H <= 0 || C <= 0) return FSCNN_ERR_SHAPE;
     if (!fits_int((long long)C * H + 1) || !fits_int((long long)W * H + 1)) return FSCNN_ERR_SHAPE;
-    return reorder_common(true, rowptr_dev, widx_dev, val_dev, C * H, W, H, (long long)W * H, C, nnz,
+    return reorder_common(true, rowptr_dev, widx_dev, val_dev, C * H, W, H, (long long)W * H, nnz,
                           tptr_dev, cidx_dev, tval_dev, workspace_dev, workspace_bytes, stream);
 }
 

@@ -165,11 +165,10 @@ hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const f
 hipError_t run_gather_fma_probe(float *scratch_dev, int iters, int blocks, hipStream_t st);
 
 // ---- transpose.hip
-long long reorder_workspace_bytes(long long n_buckets, long long n_keys);  // -1: too large
+long long reorder_workspace_bytes(long long n_buckets, long long nnz);  // -1: too large
 hipError_t launch_reorder(bool tensor, const int *rowptr, const uint32_t *idx, const float *val,
-                          int n_rows, int n_cols, int H, long long n_buckets, int n_keys,
-                          long long nnz, int *tptr, uint32_t *tidx, float *tval, void *workspace,
-                          hipStream_t st);
+                          int n_rows, int n_cols, int H, long long n_buckets, long long nnz,
+                          int *tptr, uint32_t *tidx, float *tval, void *workspace, hipStream_t st);
 
 // ---- conv_si.hip
 constexpr int kSiCC = 8;   // channels per step of the compressed activation's chunk pointers

@@ -5,11 +5,17 @@
 //   matrix, rows -> columns:   bucket = column of the node,  key = its old row;
 //   tensor, O_whc -> O_chw:    old row = c*H + h lists w;  bucket = w*H + h,  key = c.
 // The paper does this with a sequential walk that advances one cursor per new row (the vector
-// v of Alg. 3) - a stable counting sort.  The same result is computed here without any
-// order-dependent step: a bit matrix marks which (bucket, key) pairs exist, the population
-// counts of a bucket's words give the bucket sizes and, accumulated, the rank of every key
-// inside its bucket, so each node knows its final position on its own.  Integer work only;
-// values are copied bit for bit.
+// v of Alg. 3) - a stable counting sort.  The same result is computed here in passes whose
+// outcome does not depend on thread order, with scratch of O(nodes + new rows):
+//   1. count the nodes of every bucket (integer atomic adds: the sums are order-independent);
+//   2. exclusive scan of the counts = the new pointer array;
+//   3. drop every node into its bucket's segment of a scratch copy, at a position handed out by
+//      an atomic cursor - the segment then holds the right nodes in an arbitrary order;
+//   4. every node of the scratch copy counts the nodes of its segment with a smaller key - its
+//      rank, since keys are unique inside a bucket - and lands at pointer[bucket] + rank.
+// The arbitrary order of step 3 never reaches the result.  Step 4 costs the sum of the squared
+// bucket sizes (a bucket is a column of the matrix / a pixel's channel list: tens to hundreds
+// of nodes).  Integer work only; values are copied bit for bit.
 #include "internal.h"
 
 namespace fscnn {
@@ -59,102 +65,128 @@ __device__ inline Dest dest_of(int row, uint32_t col, int n_cols, int H)
 }
 
 template <bool TENSOR>
-__global__ void __launch_bounds__(kBlock) reorder_mark_kernel(const int *__restrict__ rowptr,
-                                                              const uint32_t *__restrict__ idx,
-                                                              int n_rows, int n_cols, int H,
-                                                              long long nnz, int nw,
-                                                              uint32_t *__restrict__ bits)
+__global__ void __launch_bounds__(kBlock) reorder_count_kernel(const int *__restrict__ rowptr,
+                                                               const uint32_t *__restrict__ idx,
+                                                               int n_rows, int n_cols, int H,
+                                                               long long nnz, int *__restrict__ cnt)
 {
     const long long e = (long long)blockIdx.x * kBlock + threadIdx.x;
     if (e >= nnz) return;
     const Dest d = dest_of<TENSOR>(row_of(rowptr, n_rows, e), idx[e], n_cols, H);
-    if (d.ok) atomicOr(&bits[d.bucket * nw + (d.key >> 5)], 1u << (d.key & 31));
+    if (d.ok) atomicAdd(&cnt[d.bucket], 1);
 }
 
-// Per bucket: exclusive running population count over its words, and the total.
-__global__ void __launch_bounds__(kBlock) reorder_count_kernel(const uint32_t *__restrict__ bits,
-                                                               long long n_buckets, int nw,
-                                                               int *__restrict__ before,
-                                                               int *__restrict__ cnt)
+// cursor[b] = tptr[b]: where the next node of bucket b is dropped
+__global__ void __launch_bounds__(kBlock) reorder_cursor_kernel(const int *__restrict__ tptr,
+                                                                long long n_buckets, int *__restrict__ cursor)
 {
     const long long b = (long long)blockIdx.x * kBlock + threadIdx.x;
-    if (b >= n_buckets) return;
-    int run = 0;
-    for (int w = 0; w < nw; ++w) {
-        before[b * nw + w] = run;
-        run += __popc(bits[b * nw + w]);
-    }
-    cnt[b] = run;
+    if (b < n_buckets) cursor[b] = tptr[b];
 }
 
 template <bool TENSOR>
-__global__ void __launch_bounds__(kBlock) reorder_scatter_kernel(
+__global__ void __launch_bounds__(kBlock) reorder_drop_kernel(
     const int *__restrict__ rowptr, const uint32_t *__restrict__ idx, const float *__restrict__ val,
-    int n_rows, int n_cols, int H, long long nnz, int nw, const uint32_t *__restrict__ bits,
-    const int *__restrict__ before, const int *__restrict__ tptr, uint32_t *__restrict__ tidx,
-    float *__restrict__ tval)
+    int n_rows, int n_cols, int H, long long nnz, int *__restrict__ cursor,
+    uint32_t *__restrict__ skey, float *__restrict__ sval)
 {
     const long long e = (long long)blockIdx.x * kBlock + threadIdx.x;
     if (e >= nnz) return;
     const Dest d = dest_of<TENSOR>(row_of(rowptr, n_rows, e), idx[e], n_cols, H);
     if (!d.ok) return;
-    const long long wd = d.bucket * nw + (d.key >> 5);
-    const int rank = before[wd] + __popc(bits[wd] & ((1u << (d.key & 31)) - 1u));
-    const long long dst = (long long)tptr[d.bucket] + rank;
-    if (dst < nnz) {  // holds for every well-formed input (strictly ascending indices per row)
-        tidx[dst] = (uint32_t)d.key;
-        tval[dst] = val[e];
+    const int p = atomicAdd(&cursor[d.bucket], 1);
+    if (p < nnz) {
+        skey[p] = (uint32_t)d.key;
+        sval[p] = val[e];
     }
+}
+
+// One thread per position of the scratch copy: its bucket is the segment of tptr that holds the
+// position; its rank is the number of smaller keys in that segment.
+__global__ void __launch_bounds__(kBlock) reorder_place_kernel(const int *__restrict__ tptr,
+                                                               long long n_buckets, long long total,
+                                                               const uint32_t *__restrict__ skey,
+                                                               const float *__restrict__ sval,
+                                                               uint32_t *__restrict__ tidx,
+                                                               float *__restrict__ tval)
+{
+    const long long p = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (p >= total || p >= tptr[n_buckets]) return;   // past the last node that was kept
+    // last b with tptr[b] <= p (buckets may be empty)
+    long long lo = 0, hi = n_buckets;
+    while (hi - lo > 1) {
+        const long long mid = lo + (hi - lo) / 2;
+        if (tptr[mid] <= p) lo = mid; else hi = mid;
+    }
+    const int a = tptr[lo], b = tptr[lo + 1];
+    const uint32_t key = skey[p];
+    int rank = 0;
+    for (int q = a; q < b; ++q) rank += skey[q] < key ? 1 : 0;
+    tidx[a + rank] = key;
+    tval[a + rank] = sval[p];
 }
 
 inline unsigned blocks_for(long long n) { return (unsigned)((n + kBlock - 1) / kBlock); }
 
+// scratch layout (32-bit words): cnt[n_buckets] | scan scratch | cursor[n_buckets] | skey[nnz] | sval[nnz]
+struct Layout {
+    long long cnt, scan, cursor, skey, sval, words;
+};
+inline Layout layout_of(long long n_buckets, long long nnz)
+{
+    Layout l;
+    l.cnt = 0;
+    l.scan = n_buckets;
+    l.cursor = l.scan + scan_tmp_elems(n_buckets);
+    l.skey = l.cursor + n_buckets;
+    l.sval = l.skey + nnz;
+    l.words = l.sval + nnz;
+    return l;
+}
+
 }  // namespace
 
-long long reorder_workspace_bytes(long long n_buckets, long long n_keys)
+long long reorder_workspace_bytes(long long n_buckets, long long nnz)
 {
-    if (n_buckets <= 0 || n_keys <= 0) return -1;
-    const long long nw = (n_keys + 31) / 32;
-    const long long words = n_buckets * nw;
-    if (nw > 0x7fffffffLL || words / nw != n_buckets || words > (1LL << 33)) return -1;
-    return 4 * (2 * words + n_buckets + scan_tmp_elems(n_buckets));
+    if (n_buckets <= 0 || nnz < 0 || n_buckets >= (1LL << 31) || nnz >= (1LL << 31)) return -1;
+    return 4 * layout_of(n_buckets, nnz).words;
 }
 
 hipError_t launch_reorder(bool tensor, const int *rowptr, const uint32_t *idx, const float *val,
-                          int n_rows, int n_cols, int H, long long n_buckets, int n_keys,
-                          long long nnz, int *tptr, uint32_t *tidx, float *tval, void *workspace,
-                          hipStream_t st)
+                          int n_rows, int n_cols, int H, long long n_buckets, long long nnz,
+                          int *tptr, uint32_t *tidx, float *tval, void *workspace, hipStream_t st)
 {
-    const int nw = (n_keys + 31) / 32;
-    const long long words = n_buckets * nw;
-    uint32_t *bits = static_cast<uint32_t *>(workspace);
-    int *before = reinterpret_cast<int *>(bits + words);
-    int *cnt = before + words;
-    hipLaunchKernelGGL(reorder_clear_kernel, dim3(blocks_for(words)), dim3(kBlock), 0, st, bits, words);
+    const Layout l = layout_of(n_buckets, nnz);
+    int *ws = static_cast<int *>(workspace);
+    int *cnt = ws + l.cnt, *cursor = ws + l.cursor;
+    uint32_t *skey = reinterpret_cast<uint32_t *>(ws + l.skey);
+    float *sval = reinterpret_cast<float *>(ws + l.sval);
+    hipLaunchKernelGGL(reorder_clear_kernel, dim3(blocks_for(n_buckets)), dim3(kBlock), 0, st,
+                       reinterpret_cast<uint32_t *>(cnt), n_buckets);
     if (nnz > 0) {
         if (tensor)
-            hipLaunchKernelGGL(reorder_mark_kernel<true>, dim3(blocks_for(nnz)), dim3(kBlock), 0, st,
-                               rowptr, idx, n_rows, n_cols, H, nnz, nw, bits);
+            hipLaunchKernelGGL(reorder_count_kernel<true>, dim3(blocks_for(nnz)), dim3(kBlock), 0, st,
+                               rowptr, idx, n_rows, n_cols, H, nnz, cnt);
         else
-            hipLaunchKernelGGL(reorder_mark_kernel<false>, dim3(blocks_for(nnz)), dim3(kBlock), 0, st,
-                               rowptr, idx, n_rows, n_cols, H, nnz, nw, bits);
+            hipLaunchKernelGGL(reorder_count_kernel<false>, dim3(blocks_for(nnz)), dim3(kBlock), 0, st,
+                               rowptr, idx, n_rows, n_cols, H, nnz, cnt);
     }
-    hipLaunchKernelGGL(reorder_count_kernel, dim3(blocks_for(n_buckets)), dim3(kBlock), 0, st, bits,
-                       n_buckets, nw, before, cnt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    e = launch_exclusive_scan(cnt, tptr, n_buckets, cnt + n_buckets, st);
-    if (e != hipSuccess) return e;
-    if (nnz > 0) {
-        if (tensor)
-            hipLaunchKernelGGL(reorder_scatter_kernel<true>, dim3(blocks_for(nnz)), dim3(kBlock), 0, st,
-                               rowptr, idx, val, n_rows, n_cols, H, nnz, nw, bits, before, tptr, tidx,
-                               tval);
-        else
-            hipLaunchKernelGGL(reorder_scatter_kernel<false>, dim3(blocks_for(nnz)), dim3(kBlock), 0, st,
-                               rowptr, idx, val, n_rows, n_cols, H, nnz, nw, bits, before, tptr, tidx,
-                               tval);
-    }
+    e = launch_exclusive_scan(cnt, tptr, n_buckets, ws + l.scan, st);
+    if (e != hipSuccess || nnz == 0) return e;
+    hipLaunchKernelGGL(reorder_cursor_kernel, dim3(blocks_for(n_buckets)), dim3(kBlock), 0, st, tptr,
+                       n_buckets, cursor);
+    if (tensor)
+        hipLaunchKernelGGL(reorder_drop_kernel<true>, dim3(blocks_for(nnz)), dim3(kBlock), 0, st, rowptr,
+                           idx, val, n_rows, n_cols, H, nnz, cursor, skey, sval);
+    else
+        hipLaunchKernelGGL(reorder_drop_kernel<false>, dim3(blocks_for(nnz)), dim3(kBlock), 0, st, rowptr,
+                           idx, val, n_rows, n_cols, H, nnz, cursor, skey, sval);
+    // nodes with a corrupt index were skipped: the kernel reads the number of kept nodes from the
+    // pointer array's last element and places no position beyond it
+    hipLaunchKernelGGL(reorder_place_kernel, dim3(blocks_for(nnz)), dim3(kBlock), 0, st, tptr, n_buckets,
+                       nnz, skey, sval, tidx, tval);
     return hipGetLastError();
 }
 

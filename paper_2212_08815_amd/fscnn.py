@@ -440,16 +440,16 @@ def _dev_i32(t, name):
     return t
 
 
-def sparse_transpose_workspace(new_rows, index_range):
-    return int(lib().fscnn_sparse_transpose_workspace(int(new_rows), int(index_range)))
+def sparse_transpose_workspace(new_rows, nnz):
+    return int(lib().fscnn_sparse_transpose_workspace(int(new_rows), int(nnz)))
 
 
-def _transpose(entry, rowptr, idx, val, dims, new_rows, index_range, workspace):
+def _transpose(entry, rowptr, idx, val, dims, new_rows, workspace):
     rowptr, idx, val = _dev_i32(rowptr, "rowptr"), _dev_i32(idx, "idx"), _dev_f32(val, "val")
     nnz = idx.numel()
     if val.numel() != nnz:
         raise TypeError("idx and val must have one element per stored node")
-    need = sparse_transpose_workspace(new_rows, index_range)
+    need = sparse_transpose_workspace(new_rows, nnz)
     if need < 0:
         raise FscnnError(4, entry)
     if workspace is None:
@@ -468,7 +468,7 @@ def sparse_transpose(rowptr, idx, val, n_rows, n_cols, workspace=None):
     column indices), val float32; returns (tptr, tidx, tval) CUDA tensors."""
     if rowptr.numel() != n_rows + 1:
         raise TypeError("rowptr must have n_rows + 1 elements")
-    return _transpose("fscnn_sparse_transpose", rowptr, idx, val, (n_rows, n_cols), n_cols, n_rows, workspace)
+    return _transpose("fscnn_sparse_transpose", rowptr, idx, val, (n_rows, n_cols), n_cols, workspace)
 
 
 def sparse_tensor_transpose(rowptr, widx, val, W, H, C, workspace=None):
@@ -476,7 +476,7 @@ def sparse_tensor_transpose(rowptr, widx, val, W, H, C, workspace=None):
     (row w*H+h lists c)."""
     if rowptr.numel() != C * H + 1:
         raise TypeError("rowptr must have C*H + 1 elements")
-    return _transpose("fscnn_sparse_tensor_transpose", rowptr, widx, val, (W, H, C), W * H, C, workspace)
+    return _transpose("fscnn_sparse_tensor_transpose", rowptr, widx, val, (W, H, C), W * H, workspace)
 
 
 def probe_gather_fma(iters=20000, work_groups=2048):

@@ -403,8 +403,9 @@ def test_leaky_relu_epilogue(F, case):
     """LeakyReLU on every kernel family: tiled 3x3, stride 2, 1x1, channel-split, direct."""
     n, c, k, h, w_, r, stride, pad, slope = case
     x, w, b = inputs.random_layer(sum(case[:5]) + 11, n, c, k, h, w_, r, r, 0.3)
-    o, a = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, stride, pad, b, False, want_abs=True)
-    want = np.where(o > 0, o, (o * np.float32(slope)).astype(np.float32)).astype(np.float32)
+    o = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, stride, pad, b, False)
+    want, a = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, stride, pad, b, False, want_abs=True,
+                                          leaky=slope)
     f = F.filter_compress(dev(w))
     g = host(F.conv2d_sparse_filter(f, dev(x), stride, pad, dev(b), leaky=slope))
     assert_parity(g, want, a, row_nmax(w), "leaky %r" % (case,))
@@ -596,11 +597,10 @@ def test_yolo_shaped_stack_chain(F):
         y = F.conv2d_sparse_filter(f, cur, st, pad, dev(b), leaky=L["leaky"], x_layout=F.N4, y_layout=F.N4, n=n)
         g = from_n4(host(y), n)
         csr = oracle.filter_compress(w)
-        o, a = oracle.conv2d_sparse_filter(cur_host, csr, w.shape, st, pad, b, False, want_abs=True)
-        want = np.where(o > 0, o, o * np.float32(L["leaky"])).astype(np.float32)
+        want, a = oracle.conv2d_sparse_filter(cur_host, csr, w.shape, st, pad, b, False, want_abs=True,
+                                              leaky=L["leaky"])
         assert_parity(g, want, a, row_nmax(w), "yolo layer %d" % li)
-        o2 = oracle.conv2d_sparse_filter(oc, csr, w.shape, st, pad, b, False)
-        oc = np.where(o2 > 0, o2, o2 * np.float32(L["leaky"])).astype(np.float32)
+        oc = oracle.conv2d_sparse_filter(oc, csr, w.shape, st, pad, b, False, leaky=L["leaky"])
         cur, cur_host = y, g
     assert {"st2", "r1s1"} <= kinds               # stride-2 and 1x1 configurations were exercised
     # 52 layers of fp32 rounding against the double-accumulating oracle chain

@@ -76,9 +76,8 @@ def test_random_small_problems(F, block):
         print(what, flush=True)
         x, w, b = inputs.random_layer(1000 * block + i, n, c, k, h, w_, r, s, keep, x_zero_frac=0.3,
                                       bias=bool(rng.integers(0, 2)))
-        o, a = oracle.conv2d_dense(x, w, stride, pad, b, act == "relu", want_abs=True)
-        if act == "leaky":
-            o = np.where(o > 0, o, o * np.float32(0.1)).astype(np.float32)
+        o, a = oracle.conv2d_dense(x, w, stride, pad, b, act == "relu", want_abs=True,
+                                   leaky=0.1 if act == "leaky" else None)
         f = F.filter_compress(dev(w))
         xin = dev(to_n4(x)) if lay in ("n4", "n4in") else dev(x)
         xl = F.N4 if lay in ("n4", "n4in") else F.NCHW

@@ -62,7 +62,7 @@ def test_matrix_transpose_of_a_compressed_filter_bank_and_special_values(F):
     ptr = np.array([0, 2, 2, 4], np.int32)
     idx = np.array([0, 3, 1, 3], np.uint32)
     val = np.array([np.nan, -0.0, 1e-42, np.inf], np.float32)
-    ws = torch.empty(F.sparse_transpose_workspace(4, 3) // 4 + 1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(F.sparse_transpose_workspace(4, 4) // 4 + 1, dtype=torch.int32, device="cuda")
     same(F.sparse_transpose(dev_i32(ptr), dev_i32(idx), torch.from_numpy(val).cuda(), 3, 4, workspace=ws),
          oracle.sparse_transpose(ptr, idx, val, 3, 4))
     small = torch.empty(2, dtype=torch.int32, device="cuda")
@@ -95,3 +95,32 @@ def test_tensor_transpose_chains_with_the_activation_compressor(F):
     ptr, hidx, val = csr_of(xt.reshape(C * W, H))
     got = F.sparse_tensor_transpose(dev_i32(ptr), dev_i32(hidx), torch.from_numpy(val).cuda(), H, W, C)
     same(got, (prow, cidx, xval))
+
+
+def test_large_sparse_matrix_needs_scratch_in_proportion_to_its_nodes(F):
+    """200 000 x 300 000 with about a million stored nodes: the scratch is a few bytes per node and
+    per new row (a rows x columns bit matrix would be gigabytes)."""
+    rng = np.random.default_rng(12)
+    n_rows, n_cols, per_row = 200_000, 300_000, 5
+    cols = np.sort(rng.integers(0, n_cols, (n_rows, per_row)), axis=1)
+    keep = np.ones_like(cols, bool)
+    keep[:, 1:] = cols[:, 1:] != cols[:, :-1]                      # indices strictly ascending inside a row
+    ptr = np.concatenate([[0], np.cumsum(keep.sum(1))]).astype(np.int32)
+    idx = cols[keep].astype(np.uint32)
+    val = rng.standard_normal(idx.size).astype(np.float32)
+    need = F.sparse_transpose_workspace(n_cols, idx.size)
+    assert need < 16 << 20
+    want = oracle.sparse_transpose(ptr, idx, val, n_rows, n_cols)
+    got = F.sparse_transpose(dev_i32(ptr), dev_i32(idx), torch.from_numpy(val).cuda(), n_rows, n_cols)
+    torch.cuda.synchronize()
+    same(got, want)
+
+
+def test_a_node_with_an_index_out_of_range_is_dropped(F):
+    ptr = np.array([0, 3, 5], np.int32)
+    idx = np.array([0, 2, 9, 1, 2], np.uint32)                     # 9 >= n_cols = 3
+    val = np.arange(1, 6, dtype=np.float32)
+    tptr, tidx, tval = (t.cpu().numpy() for t in F.sparse_transpose(dev_i32(ptr), dev_i32(idx),
+                                                                    torch.from_numpy(val).cuda(), 2, 3))
+    assert list(tptr) == [0, 1, 2, 4]
+    assert list(tidx[:4]) == [0, 1, 0, 1] and list(tval[:4]) == [1.0, 4.0, 2.0, 5.0]

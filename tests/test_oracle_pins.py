@@ -190,6 +190,37 @@ def test_zero_filter_bias_relu_and_linearity():
     assert np.all(yb[0, 0] == 0) and np.all(yb[0, 1] == 3)
 
 
+def test_leaky_relu_closed_form_and_against_the_pre_activation():
+    """Sec. 5 "Other layers": the activation is element-wise on the output.  All-ones input and
+    all-minus-one 3x3 filters: the pre-activation is -(taps inside the image) * C + bias, LeakyReLU
+    multiplies the negative ones by the slope; positive outputs (large bias) pass unchanged."""
+    C, H, W = 3, 5, 6
+    x = np.ones((1, C, H, W), np.float32)
+    w = -np.ones((2, C, 3, 3), np.float32)
+    b = np.array([0.5, 100.0], np.float32)
+    slope = 0.25                                       # exact in binary: no rounding in the product
+    y = oracle.conv2d_dense(x, w, (1, 1), (1, 1), b, leaky=slope)
+    ty = np.array([2] + [3] * (H - 2) + [2])
+    tx = np.array([2] + [3] * (W - 2) + [2])
+    pre = -(ty[:, None] * tx[None, :] * C).astype(np.float64)
+    assert np.array_equal(y[0, 0], ((pre + 0.5) * slope).astype(np.float32))      # all negative
+    assert np.array_equal(y[0, 1], (pre + 100.0).astype(np.float32))              # all positive
+    # generic data: equal to the formula applied to the un-activated oracle output, within the
+    # one extra rounding that route takes
+    rng = np.random.default_rng(17)
+    x = rng.standard_normal((2, 4, 7, 6)).astype(np.float32)
+    w = rng.standard_normal((3, 4, 3, 3)).astype(np.float32)
+    b = rng.standard_normal(3).astype(np.float32)
+    pre = oracle.conv2d_dense(x, w, (1, 1), (1, 1), b)
+    got = oracle.conv2d_dense(x, w, (1, 1), (1, 1), b, leaky=0.1)
+    want = np.where(pre > 0, pre, pre.astype(np.float64) * float(np.float32(0.1)))
+    assert np.all(np.abs(got - want) <= 2.0 ** -23 * np.abs(want)) and (got < 0).any() and (got > 0).any()
+    assert np.array_equal(got > 0, pre > 0)
+    flat = np.arange(0, got.size, 7)
+    assert np.array_equal(oracle.conv2d_points(x, w, flat, (1, 1), (1, 1), b, leaky=0.1), got.ravel()[flat])
+    assert np.array_equal(oracle.conv2d_dense(x, w, (1, 1), (1, 1), b, leaky=0.0), np.maximum(pre, 0))
+
+
 def test_abs_sum_and_points_agree_with_full():
     x, w, b = inputs.random_layer(11, 2, 5, 4, 9, 8, 3, 3, keep=0.5)
     y, a = oracle.conv2d_dense(x, w, (2, 1), (1, 1), b, True, want_abs=True)
