@@ -290,6 +290,19 @@ fscnn_status_t fscnn_sparse_transpose(const int *rowptr_dev, const unsigned *idx
                                       int *tptr_dev, unsigned *tidx_dev, float *tval_dev,
                                       void *workspace_dev, long long workspace_bytes, void *stream);
 
+/* fscnn_sparse_transpose for callers that cannot allocate device memory or bring a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * operands, same result, but the scratch is a static device array inside the library, 8 MiB per
+ * GPU, held until the process ends.  ERR_UNSUPPORTED when fscnn_sparse_transpose_workspace(n_cols,
+ * nnz) exceeds 8 MiB (about n_cols + nnz <= 1 000 000).  Calls no hipMalloc / hipFree and no
+ * allocating library routine, clears its counters with a kernel (no memset node) and does not
+ * synchronise.  All calls on one GPU share that GPU's array: two calls that overlap on one GPU
+ * (different streams, or threads) race; calls on one stream are ordered and safe. */
+fscnn_status_t fscnn_sparse_transpose_noalloc(const int *rowptr_dev, const unsigned *idx_dev,
+                                              const float *val_dev, int n_rows, int n_cols,
+                                              long long nnz, int *tptr_dev, unsigned *tidx_dev,
+                                              float *tval_dev, void *stream);
+
 /* Sparse 3-D tensor transpose from order O_whc to order O_chw (Sec. 4 "Sparse 3-D Tensor
  * Transpose", Alg. 4).  Input: a W x H x C tensor as C stacked matrices in order O_wh: row
  * c*H + h of rowptr_dev[C*H+1] lists in widx_dev the w of its stored nodes, strictly ascending.

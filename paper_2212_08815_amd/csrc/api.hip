@@ -758,6 +758,25 @@ fscnn_status_t fscnn_sparse_transpose(const int *rowptr_dev, const unsigned *idx
                           tptr_dev, tidx_dev, tval_dev, workspace_dev, workspace_bytes, stream);
 }
 
+fscnn_status_t fscnn_sparse_transpose_noalloc(const int *rowptr_dev, const unsigned *idx_dev,
+                                              const float *val_dev, int n_rows, int n_cols,
+                                              long long nnz, int *tptr_dev, unsigned *tidx_dev,
+                                              float *tval_dev, void *stream)
+{
+    if (n_rows <= 0 || n_cols <= 0) return FSCNN_ERR_SHAPE;
+    if (!rowptr_dev || !tptr_dev) return FSCNN_ERR_NULL;
+    if (nnz < 0 || nnz >= (1LL << 31)) return FSCNN_ERR_SHAPE;
+    const long long need = reorder_workspace_bytes(n_cols, nnz);
+    if (need < 0 || need > kStaticScratchBytes) return FSCNN_ERR_UNSUPPORTED;   // beyond the static scratch
+    int dev;
+    fscnn_status_t s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    void *ws = nullptr;
+    FSCNN_HIP(static_scratch(&ws));
+    return reorder_common(false, rowptr_dev, idx_dev, val_dev, n_rows, n_cols, 1, n_cols, nnz, tptr_dev,
+                          tidx_dev, tval_dev, ws, kStaticScratchBytes, stream);
+}
+
 fscnn_status_t fscnn_sparse_tensor_transpose(const int *rowptr_dev, const unsigned *widx_dev,
                                              const float *val_dev, int W, int H, int C,
                                              long long nnz, int *tptr_dev, unsigned *cidx_dev,

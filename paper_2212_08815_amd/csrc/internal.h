@@ -166,6 +166,10 @@ hipError_t run_gather_fma_probe(float *scratch_dev, int iters, int blocks, hipSt
 
 // ---- transpose.hip
 long long reorder_workspace_bytes(long long n_buckets, long long nnz);  // -1: too large
+// Size of the per-GPU static scratch of fscnn_sparse_transpose_noalloc, and its device address on
+// the current GPU (looked up once per device).
+constexpr long long kStaticScratchBytes = 8LL << 20;
+hipError_t static_scratch(void **ptr);
 hipError_t launch_reorder(bool tensor, const int *rowptr, const uint32_t *idx, const float *val,
                           int n_rows, int n_cols, int H, long long n_buckets, long long nnz,
                           int *tptr, uint32_t *tidx, float *tval, void *workspace, hipStream_t st);

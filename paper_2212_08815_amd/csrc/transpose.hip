@@ -144,7 +144,34 @@ inline Layout layout_of(long long n_buckets, long long nnz)
     return l;
 }
 
+// Scratch of the entry point that allocates nothing: one copy per GPU, held until the process
+// ends.  Host code never passes this name to a kernel: it is a host-side stand-in, the device
+// address comes from hipGetSymbolAddress (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+void *scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, once looked up
+
 }  // namespace
+
+hipError_t static_scratch(void **ptr)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // with `dev` current: this GPU's copy
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_ptr[dev] = p;
+    }
+    *ptr = scratch_ptr[dev];
+    return hipSuccess;
+}
 
 long long reorder_workspace_bytes(long long n_buckets, long long nnz)
 {

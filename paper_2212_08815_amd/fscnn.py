@@ -31,7 +31,7 @@ EXPORTS = [
     "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2", "fscnn_probe_gather_fma",
     "fscnn_sparse_transpose", "fscnn_sparse_tensor_transpose", "fscnn_sparse_transpose_workspace",
     "fscnn_dense_filter_prepare", "fscnn_dense_filter_destroy", "fscnn_conv2d_sparse_input_prepared",
-    "fscnn_si_variant_count", "fscnn_conv2d_sparse_filter_leaky",
+    "fscnn_si_variant_count", "fscnn_conv2d_sparse_filter_leaky", "fscnn_sparse_transpose_noalloc",
 ]
 
 NCHW, N4 = 0, 1      # fscnn_layout_t
@@ -469,6 +469,22 @@ def sparse_transpose(rowptr, idx, val, n_rows, n_cols, workspace=None):
     if rowptr.numel() != n_rows + 1:
         raise TypeError("rowptr must have n_rows + 1 elements")
     return _transpose("fscnn_sparse_transpose", rowptr, idx, val, (n_rows, n_cols), n_cols, workspace)
+
+
+def sparse_transpose_noalloc(rowptr, idx, val, n_rows, n_cols, out):
+    """fscnn_sparse_transpose_noalloc: as sparse_transpose, into the caller's `out` = (tptr, tidx,
+    tval) tensors; the binding allocates nothing either."""
+    rowptr, idx, val = _dev_i32(rowptr, "rowptr"), _dev_i32(idx, "idx"), _dev_f32(val, "val")
+    tptr, tidx, tval = _dev_i32(out[0], "tptr"), _dev_i32(out[1], "tidx"), _dev_f32(out[2], "tval")
+    nnz = idx.numel()
+    if rowptr.numel() != n_rows + 1 or val.numel() != nnz:
+        raise TypeError("rowptr must have n_rows + 1 elements, idx and val one per stored node")
+    if tptr.numel() < n_cols + 1 or tidx.numel() < nnz or tval.numel() < nnz:
+        raise TypeError("output tensors too small")
+    _check(lib().fscnn_sparse_transpose_noalloc(_ptr(rowptr), _ptr(idx), _ptr(val), _i(n_rows), _i(n_cols),
+                                                ctypes.c_longlong(nnz), _ptr(tptr), _ptr(tidx), _ptr(tval),
+                                                _stream()), "fscnn_sparse_transpose_noalloc")
+    return out
 
 
 def sparse_tensor_transpose(rowptr, widx, val, W, H, C, workspace=None):
