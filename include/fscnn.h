@@ -89,13 +89,27 @@ fscnn_status_t fscnn_filter_export(const fscnn_filter_t *f, int *rowptr_host,
  * fscnn_conv2d_sparse_filter builds the plan on first use; after that (or after this
  * call) convolution calls served by the same kernel configuration allocate nothing and do
  * not synchronise.  `variant` selects a kernel configuration (0 = automatic choice; see
- * fscnn_sf_variant_count). */
+ * fscnn_sf_variant_count).  The automatic choice depends on the tensor layouts and on the merged
+ * pool: this call prepares for NCHW tensors without pooling, fscnn_filter_prepare_ex for the call
+ * it is told about. */
 fscnn_status_t fscnn_filter_prepare(fscnn_filter_t *f, int N, int H, int W, int stride_h,
                                     int stride_w, int pad_h, int pad_w, int variant,
                                     void *stream);
 
-/* Debug / test view of the plan chosen for a geometry (builds it if needed, synchronous).
- * Writes the plan parameters into params_host[16]:
+/* The same for a convolution call with these layouts and this pool flag (the arguments of
+ * fscnn_conv2d_sparse_filter_ex / _pool2x2 / _leaky), to be issued on `stream`: builds the plan
+ * of the configuration that call will resolve to and, when the call is small enough to run in
+ * the channel-split mode (input channels divided over several work-groups, each storing its
+ * partial sums into a scratch copy of the output that a finishing pass adds up in a fixed
+ * order), that mode's scratch for `stream`.  Afterwards such calls on `stream` allocate nothing
+ * and do not synchronise, which is what a caller that captures them into a HIP graph needs.
+ * Without this call the first split-mode call of a handle on a stream allocates its scratch. */
+fscnn_status_t fscnn_filter_prepare_ex(fscnn_filter_t *f, int N, int H, int W, int stride_h,
+                                       int stride_w, int pad_h, int pad_w, fscnn_layout_t x_layout,
+                                       fscnn_layout_t y_layout, int pool, int variant, void *stream);
+
+/* Debug / test view of the plan chosen for a geometry (builds it if needed, synchronous; variant
+ * 0 resolves as for NCHW tensors without pooling).  Writes the plan parameters into params_host[16]:
  *   [0] variant id  [1] CC channels per chunk  [2] KG output channels per group
  *   [3] number of chunks  [4] number of groups  [5] tile rows per channel
  *   [6] pitch (vectors per tile row)  [7] BV floats per vector (images interleaved)

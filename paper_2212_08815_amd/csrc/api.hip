@@ -59,7 +59,42 @@ void free_plan(SfPlan *p)
     if (!p) return;
     if (p->segptr) (void)hipFree(p->segptr);
     if (p->recs) (void)hipFree(p->recs);
+    for (auto &sc : p->split)
+        if (sc.buf) (void)hipFree(sc.buf);
     delete p;
+}
+
+// Scratch of the channel-split mode for a call on `st`: the buffer this stream used before if it is
+// large enough, else a new one (the first such call of a plan on a stream allocates; replacing a
+// buffer that is too small waits for the stream's earlier work on it).  One buffer per stream:
+// calls that share a handle on different streams never share scratch.
+fscnn_status_t split_scratch(fscnn_filter_t *f, SfPlan *p, hipStream_t st, size_t bytes, float **out)
+{
+    std::lock_guard<std::mutex> lock(f->mu);
+    for (auto &sc : p->split)
+        if (sc.stream == st) {
+            if (sc.bytes < bytes) {
+                float *nb = nullptr;
+                if (hipMalloc(&nb, bytes) != hipSuccess) {
+                    (void)hipGetLastError();
+                    return FSCNN_ERR_ALLOC;
+                }
+                (void)hipStreamSynchronize(st);
+                (void)hipFree(sc.buf);
+                sc.buf = nb;
+                sc.bytes = bytes;
+            }
+            *out = sc.buf;
+            return FSCNN_OK;
+        }
+    float *nb = nullptr;
+    if (hipMalloc(&nb, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return FSCNN_ERR_ALLOC;
+    }
+    p->split.push_back({st, nb, bytes});
+    *out = nb;
+    return FSCNN_OK;
 }
 
 // Returns the plan of `variant` (>= 1) for this handle, building it on `st` when absent.
@@ -276,20 +311,43 @@ fscnn_status_t fscnn_filter_export(const fscnn_filter_t *f, int *rowptr_host, un
     return FSCNN_OK;
 }
 
-fscnn_status_t fscnn_filter_prepare(fscnn_filter_t *f, int N, int H, int W, int sh, int sw, int ph,
-                                    int pw, int variant, void *stream)
+fscnn_status_t fscnn_filter_prepare_ex(fscnn_filter_t *f, int N, int H, int W, int sh, int sw, int ph,
+                                       int pw, fscnn_layout_t x_layout, fscnn_layout_t y_layout, int pool,
+                                       int variant, void *stream)
 {
     if (!f) return FSCNN_ERR_NULL;
     if (!live(f)) return FSCNN_ERR_HANDLE;
     if (N <= 0) return FSCNN_ERR_SHAPE;
+    if ((x_layout != FSCNN_LAYOUT_NCHW && x_layout != FSCNN_LAYOUT_N4) ||
+        (y_layout != FSCNN_LAYOUT_NCHW && y_layout != FSCNN_LAYOUT_N4))
+        return FSCNN_ERR_UNSUPPORTED;
     int Ho, Wo;
     fscnn_status_t s = out_shape(H, W, f->R, f->S, sh, sw, ph, pw, &Ho, &Wo);
     if (s != FSCNN_OK) return s;
+    const int in4 = x_layout == FSCNN_LAYOUT_N4, out4 = y_layout == FSCNN_LAYOUT_N4;
     int v;
-    s = resolve_variant(f, N, H, W, sh, sw, variant, &v);
+    s = resolve_variant(f, N, H, W, sh, sw, variant, &v, in4 || out4, pool != 0);
     if (s != FSCNN_OK) return s;
+    if ((in4 || out4 || pool) && v < 0) return FSCNN_ERR_UNSUPPORTED;
+    if (v > 0 && !sf_variant_has_layout(v, in4, out4, pool)) return FSCNN_ERR_UNSUPPORTED;
     SfPlan *p;
-    return get_plan(f, v, (hipStream_t)stream, &p);
+    s = get_plan(f, v, (hipStream_t)stream, &p);
+    if (s != FSCNN_OK || p->direct) return s;
+    // the same decision as the convolution call takes
+    const int csplit = (variant == 0 && !pool) ? sf_choose_csplit(v, N, f->K, Ho, Wo, p->NCH) : 1;
+    if (csplit > 1) {
+        float *parts;
+        s = split_scratch(f, p, (hipStream_t)stream,
+                          sizeof(float) * (size_t)csplit * (size_t)sf_split_elems(N, f->K, Ho, Wo, out4), &parts);
+    }
+    return s;
+}
+
+fscnn_status_t fscnn_filter_prepare(fscnn_filter_t *f, int N, int H, int W, int sh, int sw, int ph,
+                                    int pw, int variant, void *stream)
+{
+    return fscnn_filter_prepare_ex(f, N, H, W, sh, sw, ph, pw, FSCNN_LAYOUT_NCHW, FSCNN_LAYOUT_NCHW, 0, variant,
+                                   stream);
 }
 
 fscnn_status_t fscnn_filter_plan_export(fscnn_filter_t *f, int N, int H, int W, int sh, int sw,
@@ -404,8 +462,14 @@ static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int 
     } else {
         // automatic choice only: an explicitly selected configuration runs as it is
         const int csplit = (variant == 0 && !pool) ? sf_choose_csplit(v, N, f->K, Ho, Wo, p->NCH) : 1;
+        float *parts = nullptr;
+        if (csplit > 1) {
+            s = split_scratch(f, p, st, sizeof(float) * (size_t)csplit * (size_t)sf_split_elems(N, f->K, Ho, Wo, out4),
+                              &parts);
+            if (s != FSCNN_OK) return s;
+        }
         FSCNN_HIP(launch_conv_sf_tiled(*p, x_dev, N, C, H, W, f->K, Ho, Wo, ph, pw, bias_dev, relu,
-                                       y_dev, in4, out4, pool, csplit, st));
+                                       y_dev, in4, out4, pool, csplit, parts, st));
     }
     return FSCNN_OK;
 }

@@ -157,21 +157,22 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                      const float *__restrict__ bias, const Rec *__restrict__ recs,
                      const int *__restrict__ segptr, int N, int C, int H, int W, int K, int Ho,
                      int Wo, int ph, int pw, int relu, int NCH, int NG, int tiles_x,
-                     int tiles_per_img, int nblk, int csplit)
+                     int tiles_per_img, int nblk, int csplit, long long part_stride)
 {
     using V = typename VecT<G::BV>::T;
     extern __shared__ __align__(256) char ldsb[];
 
     // csplit > 1 (small problems): the input-channel chunks are divided among csplit
-    // work-groups per (tile, channel group); each adds its partial sums into a zeroed y and a
-    // separate pass applies bias and ReLU
+    // work-groups per (tile, channel group); part cs stores its partial sums (no bias, no
+    // activation) into its own copy of the output, y + cs * part_stride, and a separate pass adds
+    // the copies up in the order of the parts: one writer per element, the same bits on every run
     const int lid0 = xcd_remap(blockIdx.x, nblk);
     const int cs = lid0 % csplit;
     const int lid = lid0 / csplit;
     const int cper = (NCH + csplit - 1) / csplit;
-    const int ci0 = cs * cper;
+    const int ci0 = cs * cper < NCH ? cs * cper : NCH;   // a part past the last chunk stores zeros
     const int ci1 = ci0 + cper < NCH ? ci0 + cper : NCH;
-    if (ci0 >= ci1) return;  // the whole work-group: nothing to add
+    if (csplit > 1) y += (long long)cs * part_stride;
     const int kg = lid % NG;
     const int t = (lid / NG) % tiles_per_img;
     const int n0 = (lid / (NG * tiles_per_img)) * G::IMGS;
@@ -245,6 +246,8 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
         for (int p = 0; p < G::P; ++p) acc[j][p] = 0.0f;
 
     // this wave's record stream, its (chunk, slot) boundaries, and the SGPR queue of records
+    // (ci0 == NCH, an empty part: the entry read here is the next wave's first, or the array's
+    // last one; no record is applied)
     const int *seg = segptr + ((long long)(kg * G::WAVES + wave) * NCH + ci0) * G::SLOTS;
     int i = seg[0];
     Rec q[G::FIFO];
@@ -252,7 +255,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     for (int f = 0; f < G::FIFO; ++f) q[f] = recs[i + f];
     int bnd[G::SLOTS];
 #pragma unroll
-    for (int j = 0; j < G::SLOTS; ++j) bnd[j] = seg[j + 1];
+    for (int j = 0; j < G::SLOTS; ++j) bnd[j] = ci0 < ci1 ? seg[j + 1] : i;
 
     // the first D chunks start loading; chunk 0 must have landed before anyone reads it
 #pragma unroll
@@ -504,9 +507,8 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                 const int oy = ty0 + lh * G::NV + v;
                 if (n < N && oy < Ho && ox < Wo) {
                     if (csplit > 1) {  // partial sums of this channel range
-                        float *dst = reinterpret_cast<float *>(yk + (long long)oy * Wo + ox);
-#pragma unroll
-                        for (int b = 0; b < 4; ++b) atomicAdd(dst + b, acc[j][v * 4 + b]);
+                        yk[(long long)oy * Wo + ox] =
+                            make_float4(acc[j][v * 4], acc[j][v * 4 + 1], acc[j][v * 4 + 2], acc[j][v * 4 + 3]);
                         continue;
                     }
                     float r[4];
@@ -528,7 +530,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                     const int oy = ty0 + lh * G::NV + v;
                     if (n < N && oy < Ho && ox < Wo) {
                         if (csplit > 1) {
-                            atomicAdd(yk + (long long)oy * Wo + ox, acc[j][v * G::BV + b]);
+                            yk[(long long)oy * Wo + ox] = acc[j][v * G::BV + b];
                             continue;
                         }
                         float r = acc[j][v * G::BV + b] + bk;
@@ -577,35 +579,30 @@ conv_sf_direct_kernel(const int *__restrict__ rowptr, const uint32_t *__restrict
     y[(((long long)n * K + k) * Ho + oy) * Wo + ox] = acc;
 }
 
-// Helpers of the channel-split mode.
-__global__ void __launch_bounds__(256) fill_zero_kernel(float *__restrict__ y, long long n)
-{
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) y[i] = 0.0f;
-}
-
-// y = max(y + bias[k], 0): element i belongs to channel (i / (plane * inner)) % K, where inner is
-// 1 for NCHW and 4 for the batch-interleaved layout.
-__global__ void __launch_bounds__(256) bias_relu_kernel(float *__restrict__ y, const float *__restrict__ bias,
+// Finishing pass of the channel-split mode: y = act(bias[k] + part 0 + part 1 + ...), the parts
+// added in their order.  Element i belongs to channel (i / (plane * inner)) % K, where inner is 1
+// for NCHW and 4 for the batch-interleaved layout.
+__global__ void __launch_bounds__(256) split_sum_kernel(const float *__restrict__ parts, int nparts,
+                                                        long long part_stride, const float *__restrict__ bias,
                                                         int K, long long plane, int inner, int relu,
-                                                        long long n)
+                                                        long long n, float *__restrict__ y)
 {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
-    float v = y[i];
+    float v = parts[i];
+    for (int p = 1; p < nparts; ++p) v += parts[(long long)p * part_stride + i];
     if (bias) v += bias[(int)((i / (plane * inner)) % K)];
-    v = act_apply(v, relu);
-    y[i] = v;
+    y[i] = act_apply(v, relu);
 }
 
 // ---------------------------------------------------------------- variant table
 using LaunchFn = hipError_t (*)(const SfPlan &, const float *, int, int, int, int, int, int, int,
-                                int, int, const float *, int, float *, int, hipStream_t);
+                                int, int, const float *, int, float *, int, long long, hipStream_t);
 
 template <class G>
 hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K, int Ho,
                         int Wo, int ph, int pw, const float *bias, int relu, float *y, int csplit,
-                        hipStream_t st)
+                        long long part_stride, hipStream_t st)
 {
     static_assert(G::LDS_BYTES <= 160 * 1024, "tile exceeds the 160 KB LDS of a gfx950 CU");
     if (G::LDS_BYTES > 64 * 1024) {
@@ -622,7 +619,7 @@ hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, in
     if (nblk <= 0 || nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(conv_sf_tiled_kernel<G>, dim3((unsigned)nblk), dim3(G::NT), G::LDS_BYTES, st,
                        x, y, bias, p.recs, p.segptr, N, C, H, W, K, Ho, Wo, ph, pw, relu, p.NCH,
-                       p.NG, tiles_x, tiles_x * tiles_y, (int)nblk, csplit);
+                       p.NG, tiles_x, tiles_x * tiles_y, (int)nblk, csplit, part_stride);
     return hipGetLastError();
 }
 
@@ -870,9 +867,15 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int strid
     return best;
 }
 
+long long sf_split_elems(int N, int K, int Ho, int Wo, int out4)
+{
+    return (out4 ? ((long long)N + 3) / 4 * 4 : (long long)N) * K * Ho * Wo;
+}
+
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
-                                float *y, int in4, int out4, int pool, int csplit, hipStream_t st)
+                                float *y, int in4, int out4, int pool, int csplit, float *parts,
+                                hipStream_t st)
 {
     int n;
     const Variant *t = variants(&n);
@@ -881,35 +884,36 @@ hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, i
     LaunchFn fn = (pool ? v.pool : v.fn)[in4 ? 1 : 0][out4 ? 1 : 0];
     if (!fn) return hipErrorInvalidValue;
     if (csplit > 1) {
-        // partial sums are added into y: clear it first, finish with bias and ReLU afterwards
-        const long long total = (out4 ? ((long long)N + 3) / 4 * 4 : (long long)N) * K * Ho * Wo;
-        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, y, total);
-        hipError_t e = fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, csplit, st);
+        // every part stores its partial sums into its own copy of the output (parts: csplit *
+        // sf_split_elems floats of scratch), then one pass adds the copies, bias and activation
+        if (!parts) return hipErrorInvalidValue;
+        const long long total = sf_split_elems(N, K, Ho, Wo, out4);
+        hipError_t e = fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, parts, csplit, total, st);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(bias_relu_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, y, bias,
-                           K, (long long)Ho * Wo, out4 ? 4 : 1, relu, total);
+        hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, parts,
+                           csplit, total, bias, K, (long long)Ho * Wo, out4 ? 4 : 1, relu, total, y);
         return hipGetLastError();
     }
-    return fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, 1, st);
+    return fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, 1, 0, st);
 }
 
 // How many ways the input channels are split for a launch: small problems (deep layers at small
 // batch) leave most of the 256 CUs idle and serialise hundreds of channels in a few groups;
-// splitting the chunk range restores parallelism at the price of atomic adds into y and a
-// finishing pass, which only pays while y is small (measured: 14x14 and 28x28 at N <= 8 gain up
-// to 3.7x, 56x56 and wider lose).
+// splitting the chunk range restores parallelism at the price of one copy of the output per part
+// and a finishing pass that adds them up, which only pays while y is small (measured: 14x14 and
+// 28x28 at N <= 8 gain up to 3.7x, 56x56 and wider lose).
 int sf_choose_csplit(int variant, int N, int K, int Ho, int Wo, int NCH)
 {
     int n;
     const Variant *t = variants(&n);
     if (variant < 1 || variant > n) return 1;
     const long long b = sf_blocks(t[variant - 1].g, N, K, Ho, Wo);
-    if (b > 128 || NCH < 4) return 1;   // with more groups the atomics cost more than they gain
+    if (b > 128 || NCH < 4) return 1;   // with more groups the extra passes cost more than they gain
     long long s = (256 + b - 1) / b;
     if (s > NCH / 2) s = NCH / 2;   // at least two chunks per part
     if (s > 8) s = 8;
     const long long outputs = (long long)N * K * Ho * Wo;
-    if (s * outputs > (4LL << 20)) s = (4LL << 20) / outputs;   // bound the atomic traffic
+    if (s * outputs > (4LL << 20)) s = (4LL << 20) / outputs;   // bound the scratch and its traffic
     return s < 1 ? 1 : (int)s;
 }
 

@@ -66,6 +66,14 @@ struct SfPlan {
     long long nrec = 0;       // records (= nonzeros); the array carries kPlanSpare spare entries
     int *segptr = nullptr;    // [NG*NCH*KG + 1], bucket order (group, wave, chunk, slot)
     Rec *recs = nullptr;      // [nrec + kPlanSpare]
+    // Scratch of the channel-split mode (small problems): one buffer per stream that has used the
+    // plan in that mode, so that calls on different streams never share one.  Grown on demand.
+    struct SplitScratch {
+        hipStream_t stream;
+        float *buf;
+        size_t bytes;
+    };
+    std::vector<SplitScratch> split;
 };
 
 struct SiGeom {
@@ -152,9 +160,12 @@ const char *sf_variant_name(int variant);
 bool sf_variant_geom(int variant, int R, int S, int sh, int sw, SfGeom *g);
 int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool, bool n4);
 bool sf_variant_has_layout(int variant, int in4, int out4, int pool);
+// csplit > 1: `parts` is scratch of csplit * sf_split_elems(...) floats (one copy of y per part)
+long long sf_split_elems(int N, int K, int Ho, int Wo, int out4);
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
-                                float *y, int in4, int out4, int pool, int csplit, hipStream_t st);
+                                float *y, int in4, int out4, int pool, int csplit, float *parts,
+                                hipStream_t st);
 // 1, or the number of parts the input-channel range is split into for a small problem
 int sf_choose_csplit(int variant, int N, int K, int Ho, int Wo, int NCH);
 hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const float *val,

@@ -32,6 +32,7 @@ EXPORTS = [
     "fscnn_sparse_transpose", "fscnn_sparse_tensor_transpose", "fscnn_sparse_transpose_workspace",
     "fscnn_dense_filter_prepare", "fscnn_dense_filter_destroy", "fscnn_conv2d_sparse_input_prepared",
     "fscnn_si_variant_count", "fscnn_conv2d_sparse_filter_leaky", "fscnn_sparse_transpose_noalloc",
+    "fscnn_filter_prepare_ex",
 ]
 
 NCHW, N4 = 0, 1      # fscnn_layout_t
@@ -170,10 +171,13 @@ def filter_export(f):
     return rowptr, idx, val
 
 
-def filter_prepare(f, N, H, W, stride=(1, 1), pad=(0, 0), variant=0):
-    _check(lib().fscnn_filter_prepare(f.handle, _i(N), _i(H), _i(W), _i(stride[0]), _i(stride[1]),
-                                      _i(pad[0]), _i(pad[1]), _i(variant), _stream()),
-           "fscnn_filter_prepare")
+def filter_prepare(f, N, H, W, stride=(1, 1), pad=(0, 0), variant=0, x_layout=NCHW, y_layout=NCHW, pool=False):
+    """fscnn_filter_prepare_ex: plan (and, for small problems, the channel-split scratch of the
+    current stream) of the convolution call with these arguments."""
+    _check(lib().fscnn_filter_prepare_ex(f.handle, _i(N), _i(H), _i(W), _i(stride[0]), _i(stride[1]),
+                                         _i(pad[0]), _i(pad[1]), _i(x_layout), _i(y_layout), _i(1 if pool else 0),
+                                         _i(variant), _stream()),
+           "fscnn_filter_prepare_ex")
 
 
 def filter_plan_export(f, N, H, W, stride=(1, 1), pad=(0, 0), variant=0):

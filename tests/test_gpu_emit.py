@@ -89,15 +89,10 @@ def test_emit_random_data_matches_oracle(F, case):
     clear = np.abs(pre) > (c * r * s_ + 2) * 2.0 ** -22 * pa
     assert clear.mean() > 0.9
     assert np.array_equal((yd != 0)[clear], (pre > 0)[clear])
-    # without the dense copy (a temporary inside the call): the same values up to the last bits
-    # (small problems may run in the channel-split mode, whose partial sums arrive in no fixed
-    # order), and a well-formed structure
+    # without the dense copy: the same handle contents, bit for bit (one writer per output element)
     s2 = F.conv2d_sparse_filter_emit(f, dev(x), stride, pad, dev(b), True)
     p2, c2, v2 = F.input_export(s2)
-    assert p2[0] == 0 and np.all(np.diff(p2) >= 0) and p2[-1] == s2.nnz == c2.size == v2.size
-    assert np.all(v2 != 0)
-    assert_parity(densify(p2, c2, v2, o.shape), o, a, c * r * s_, "emit without dense copy %r" % (case,))
-    assert np.array_equal((densify(p2, c2, v2, o.shape) != 0)[clear], (pre > 0)[clear])
+    assert np.array_equal(p2, prow) and np.array_equal(c2, cidx) and np.array_equal(bits(v2), bits(val))
 
 
 def test_emit_chains_into_the_sparse_input_convolution(F):
