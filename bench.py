@@ -232,10 +232,13 @@ def other_rows(fscnn, torch, inputs, np, dev_layers):
             # ReLU output compressed (a dense temporary inside), next to the convolution alone
             ms_e = time_gpu(torch, lambda: fscnn.conv2d_sparse_filter_emit(f, x, (1, 1), (1, 1), b, True), 5)
             es = fscnn.conv2d_sparse_filter_emit(f, x, (1, 1), (1, 1), b, True)
+            ms_i = time_gpu(torch, lambda: fscnn.conv2d_sparse_filter_emit(f, x, (1, 1), (1, 1), b, True, into=es), 5)
             out["conv2d_sparse_filter_emit"] = dict(
-                ms=ms_e, conv_alone_ms=ms, nnz_out=es.nnz, density_out=es.nnz / y.numel(),
+                ms=ms_i, ms_with_allocation=ms_e, conv_alone_ms=ms, nnz_out=es.nnz, density_out=es.nnz / y.numel(),
                 note="same layer at 95 % weight sparsity: convolution + ReLU + compression of the result "
-                     "in one call; incl. allocations and two host syncs")
+                     "(counted in the convolution's epilogue, one scan, one fill); ms = refilling a handle "
+                     "(fscnn_conv2d_sparse_filter_emit_into), ms_with_allocation = a new handle per call "
+                     "(one hipMalloc and the previous handle's hipFree)")
             x32 = torch.from_numpy(np.concatenate([c["x"]] * 4, 0)).cuda()
             xs32 = fscnn.input_compress(x32)
             y32 = fscnn.conv2d_sparse_input_prepared(xs32, dw, (1, 1), (1, 1), b, True)

@@ -235,18 +235,35 @@ fscnn_status_t fscnn_input_destroy(fscnn_input_t *in);
  * does (NCHW x, bias nullable, relu as there) and returns it compressed as
  * fscnn_input_compress would: a handle of shape N x K x Ho x Wo whose pixel rows list the
  * (channel, value) pairs with y != 0.0f.  y_dev may be NULL; if it is not, the dense
- * N x K x Ho x Wo result is left there as well (caller-owned, must not alias x).  With
- * y_dev NULL the call allocates and frees a dense temporary of that size (and waits for
- * `stream` before freeing it).  Allocates the handle's buffers and synchronises `stream`
- * (the number of stored values sizes them); with y_dev given, x_dev and y_dev must stay
- * valid until the work queued on `stream` has run, as for fscnn_input_compress;
- * *out is owned by the caller (fscnn_input_destroy).  Errors as the two calls it stands
- * for; on error *out is untouched. */
+ * N x K x Ho x Wo result is left there as well (caller-owned, must not alias x); with
+ * y_dev NULL the dense result lives inside the handle's allocation.  The non-zero results are
+ * counted in the convolution's own epilogue (per pixel and step of 8 output channels) where
+ * the launch allows it -- small problems that run in the channel-split mode, and geometries
+ * served by the direct kernel, count in a pass over the dense result instead -- then one scan and
+ * one pass that writes the pairs.  The call makes ONE device allocation, sized for the worst
+ * case (every result non-zero: 8 bytes per result), and does not wait for the device: it is
+ * asynchronous on `stream`, x_dev (and y_dev) must stay valid until the work queued on
+ * `stream` has run, and the library orders every later use of the handle, on any stream,
+ * behind the pass that fills it.  fscnn_input_info / fscnn_input_export wait for that pass when
+ * they are asked for the number of stored values.  *out is owned by the caller
+ * (fscnn_input_destroy).  Errors as the two calls it stands for; on error *out is untouched. */
 fscnn_status_t fscnn_conv2d_sparse_filter_emit(fscnn_filter_t *f, const float *x_dev, int N, int C,
                                                int H, int W, int stride_h, int stride_w,
                                                int pad_h, int pad_w, const float *bias_dev,
                                                int relu, float *y_dev, void *stream,
                                                fscnn_input_t **out);
+/* The same into a handle that an earlier fscnn_conv2d_sparse_filter_emit returned for a result
+ * of the same shape N x K x Ho x Wo (else FSCNN_ERR_MISMATCH; a handle of another origin:
+ * FSCNN_ERR_UNSUPPORTED; y_dev NULL with a handle made with a y_dev: FSCNN_ERR_NULL): the
+ * handle's previous contents are replaced.  Allocates nothing and does not wait for the
+ * device -- the form for a loop that runs the same layer again and again.  The caller orders
+ * the call behind every use of the handle's previous contents (stream order on one stream
+ * suffices); on error the handle's contents are undefined but it can be refilled or destroyed. */
+fscnn_status_t fscnn_conv2d_sparse_filter_emit_into(fscnn_filter_t *f, const float *x_dev, int N,
+                                                    int C, int H, int W, int stride_h,
+                                                    int stride_w, int pad_h, int pad_w,
+                                                    const float *bias_dev, int relu, float *y_dev,
+                                                    void *stream, fscnn_input_t *into);
 
 /* Sparse-input convolution (Sec. 4, last paragraph of "Sparse Tensor Convolution": the
  * loops of Alg. 1 with a sparse T_I and dense filters; zero activations are skipped):

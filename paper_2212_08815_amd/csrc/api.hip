@@ -186,6 +186,23 @@ fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int
     return FSCNN_OK;
 }
 
+// Number of stored values of a compressed activation.  A handle made without a host synchronisation
+// (sparse output emission) learns it here: wait for the pass that filled it, read the pointer array's
+// last element.  Returns -1 on a runtime error.
+long long input_nnz(const fscnn_input_t *in)
+{
+    if (in->nnz >= 0) return in->nnz;
+    int total = 0;
+    const size_t last = (size_t)in->N * in->H * in->W * (size_t)in->NCH;
+    if (hipEventSynchronize(in->filled) != hipSuccess ||
+        hipMemcpy(&total, in->cptr + last, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return -1;
+    }
+    const_cast<fscnn_input_t *>(in)->nnz = total;   // a cache of what the device holds
+    return total;
+}
+
 // Orders work on `st` behind the pass that fills a compressed-activation handle (it runs on the
 // stream the handle was made on and may still be in flight).
 hipError_t after_fill(const fscnn_input_t *in, hipStream_t st)
@@ -426,11 +443,16 @@ fscnn_status_t fscnn_sf_variant_choice(const fscnn_filter_t *f, int N, int H, in
     return resolve_variant(f, N, H, W, sh, sw, 0, variant_out, n4 != 0, pool != 0);
 }
 
+// emit_cnt / counted: sparse output emission.  When the launch that serves the call can count the
+// non-zero results per (pixel, step of 8 channels) in its epilogue it writes them to emit_cnt and
+// sets *counted; otherwise the caller counts in a pass of its own.
 static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int N, int C, int H,
                                      int W, int sh, int sw, int ph, int pw, const float *bias_dev,
                                      int relu, float *y_dev, fscnn_layout_t x_layout,
-                                     fscnn_layout_t y_layout, int variant, int pool, void *stream)
+                                     fscnn_layout_t y_layout, int variant, int pool, void *stream,
+                                     int *emit_cnt = nullptr, bool *counted = nullptr)
 {
+    if (counted) *counted = false;
     int Ho, Wo;
     fscnn_status_t s = check_conv_args(f, x_dev, N, C, H, W, sh, sw, ph, pw, y_dev, &Ho, &Wo);
     if (s != FSCNN_OK) return s;
@@ -468,8 +490,10 @@ static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int 
                               &parts);
             if (s != FSCNN_OK) return s;
         }
+        int *cnt = (emit_cnt && csplit == 1 && !out4 && !pool) ? emit_cnt : nullptr;
         FSCNN_HIP(launch_conv_sf_tiled(*p, x_dev, N, C, H, W, f->K, Ho, Wo, ph, pw, bias_dev, relu,
-                                       y_dev, in4, out4, pool, csplit, parts, st));
+                                       y_dev, in4, out4, pool, csplit, parts, cnt, st));
+        if (counted) *counted = cnt != nullptr;
     }
     return FSCNN_OK;
 }
@@ -593,8 +617,7 @@ static fscnn_status_t compress_activations(const float *x_dev, int N, int C, int
         if (e == hipSuccess) {
             in->cidx = static_cast<uint32_t *>(in->node_block);
             in->xval = reinterpret_cast<float *>(static_cast<char *>(in->node_block) + val_at);
-            e = launch_input_fill(x_dev, N, C, H, W, CC, NCH, in->cptr, in->cidx, in->xval, total,
-                                  kSiSpare, st);
+            e = launch_input_fill(x_dev, N, C, H, W, CC, NCH, in->cptr, in->cidx, in->xval, kSiSpare, st);
         }
     }
     if (e == hipSuccess) e = hipEventCreateWithFlags(&in->filled, hipEventDisableTiming);
@@ -620,38 +643,147 @@ fscnn_status_t fscnn_input_compress(const float *x_dev, int N, int C, int H, int
     return compress_activations(x_dev, N, C, H, W, (hipStream_t)stream, out);
 }
 
+namespace {
+
+// Where the parts of an emitted handle's one allocation start (256-byte aligned parts): pointer
+// array | counts + scan scratch | indices | values | the dense result when the caller takes none.
+struct EmitLayout {
+    long long nstep, dense;
+    size_t cnt_at, idx_at, val_at, y_at;
+    size_t bytes(bool with_y) const { return y_at + (with_y ? sizeof(float) * (size_t)dense : 0); }
+};
+
+EmitLayout emit_layout(long long npix, int K, int NCH)
+{
+    EmitLayout L;
+    L.nstep = npix * NCH;
+    L.dense = npix * K;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    L.cnt_at = up((size_t)(L.nstep + 1) * sizeof(int));
+    L.idx_at = L.cnt_at + up(sizeof(int) * (size_t)(L.nstep + scan_tmp_elems(L.nstep)));
+    L.val_at = L.idx_at + up(sizeof(uint32_t) * (size_t)(L.dense + kSiSpare));
+    L.y_at = L.val_at + up(sizeof(float) * (size_t)(L.dense + kSiSpare));
+    return L;
+}
+
+// Argument checks shared by the two emitting calls; fills the result's shape.
+fscnn_status_t emit_check(fscnn_filter_t *f, int N, int C, int H, int W, int sh, int sw, int ph,
+                          int pw, int *Ho, int *Wo, int *NCH)
+{
+    if (!live(f)) return FSCNN_ERR_HANDLE;
+    if (N <= 0 || C <= 0) return FSCNN_ERR_SHAPE;
+    fscnn_status_t s = out_shape(H, W, f->R, f->S, sh, sw, ph, pw, Ho, Wo);
+    if (s != FSCNN_OK) return s;
+    const long long npix = (long long)N * *Ho * *Wo, dense = npix * f->K;
+    if (!fits_int(dense) || !fits_int(dense + kSiSpare)) return FSCNN_ERR_UNSUPPORTED;
+    *NCH = (f->K + kSiCC - 1) / kSiCC;
+    if (!fits_int(npix * *NCH + 1) || *NCH > 8192 / kSiCC) return FSCNN_ERR_UNSUPPORTED;
+    return FSCNN_OK;
+}
+
+// The work of an emitting call on a handle whose allocation is in place: the convolution with its
+// bias / activation epilogue (which, where the launch can, counts the non-zero results per pixel
+// and step of 8 channels itself), else a count pass, one scan, one pass that writes the pairs.
+fscnn_status_t emit_run(fscnn_filter_t *f, const float *x_dev, int N, int C, int H, int W, int sh,
+                        int sw, int ph, int pw, const float *bias_dev, int relu, float *y_dev,
+                        void *stream, fscnn_input_t *in)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const int K = f->K, Ho = in->H, Wo = in->W;
+    const EmitLayout L = emit_layout((long long)N * Ho * Wo, K, in->NCH);
+    char *base = static_cast<char *>(in->ptr_block);
+    int *cnt = reinterpret_cast<int *>(base + L.cnt_at);
+    float *y = y_dev ? y_dev : reinterpret_cast<float *>(base + L.y_at);
+    bool counted = false;
+    fscnn_status_t s = conv_sf_common(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, relu, y,
+                                      FSCNN_LAYOUT_NCHW, FSCNN_LAYOUT_NCHW, 0, 0, stream, cnt, &counted);
+    if (s != FSCNN_OK) return s;
+    hipError_t e = hipSuccess;
+    if (!counted) e = launch_input_count(y, N, K, Ho, Wo, in->CC, in->NCH, cnt, st);
+    if (e == hipSuccess) e = launch_exclusive_scan(cnt, in->cptr, L.nstep, cnt + L.nstep, st);
+    if (e == hipSuccess)
+        e = launch_input_fill(y, N, K, Ho, Wo, in->CC, in->NCH, in->cptr, in->cidx, in->xval, kSiSpare, st);
+    if (e == hipSuccess) e = hipEventRecord(in->filled, st);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return e == hipErrorOutOfMemory ? FSCNN_ERR_ALLOC : FSCNN_ERR_DEVICE;
+    }
+    in->nnz = -1;
+    in->made_on = st;
+    return FSCNN_OK;
+}
+
+}  // namespace
+
 fscnn_status_t fscnn_conv2d_sparse_filter_emit(fscnn_filter_t *f, const float *x_dev, int N, int C,
                                                int H, int W, int sh, int sw, int ph, int pw,
                                                const float *bias_dev, int relu, float *y_dev,
                                                void *stream, fscnn_input_t **out)
 {
     if (!f || !x_dev || !out) return FSCNN_ERR_NULL;
-    if (!live(f)) return FSCNN_ERR_HANDLE;
-    if (N <= 0 || C <= 0) return FSCNN_ERR_SHAPE;
-    int Ho, Wo;
-    fscnn_status_t s = out_shape(H, W, f->R, f->S, sh, sw, ph, pw, &Ho, &Wo);
+    int Ho, Wo, NCH;
+    fscnn_status_t s = emit_check(f, N, C, H, W, sh, sw, ph, pw, &Ho, &Wo, &NCH);
     if (s != FSCNN_OK) return s;
-    if (!fits_int((long long)N * f->K * Ho * Wo)) return FSCNN_ERR_UNSUPPORTED;
-    float *tmp = nullptr;
-    if (!y_dev) {
-        int dev;
-        s = have_device(&dev);
-        if (s != FSCNN_OK) return s;
-        if (hipMalloc(&tmp, sizeof(float) * (size_t)N * f->K * Ho * Wo) != hipSuccess) {
-            (void)hipGetLastError();
-            return FSCNN_ERR_ALLOC;
-        }
+    int dev;
+    s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    fscnn_input_t *in = new (std::nothrow) fscnn_input();
+    if (!in) return FSCNN_ERR_ALLOC;
+    in->magic = kInputMagic;
+    in->device = dev;
+    in->N = N; in->C = f->K; in->H = Ho; in->W = Wo;
+    in->nnz = -1; in->CC = kSiCC; in->NCH = NCH;
+    in->ptr_block = nullptr; in->node_block = nullptr;
+    in->made_on = (hipStream_t)stream; in->filled = nullptr;
+    // ONE allocation, sized for the worst case (every result non-zero), so that nothing here waits
+    // for the device
+    const EmitLayout L = emit_layout((long long)N * Ho * Wo, f->K, NCH);
+    in->emit_bytes = L.bytes(y_dev == nullptr);
+    in->emit_has_y = y_dev == nullptr;
+    hipError_t e = hipMalloc(&in->ptr_block, in->emit_bytes);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&in->filled, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        if (in->ptr_block) (void)hipFree(in->ptr_block);
+        delete in;
+        return FSCNN_ERR_ALLOC;
     }
-    float *y = y_dev ? y_dev : tmp;
-    s = conv_sf_common(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, relu, y, FSCNN_LAYOUT_NCHW,
-                       FSCNN_LAYOUT_NCHW, 0, 0, stream);
-    if (s == FSCNN_OK) s = compress_activations(y, N, f->K, Ho, Wo, (hipStream_t)stream, out);
-    if (tmp) {
-        // the last pass over the temporary may still be running
-        (void)hipStreamSynchronize((hipStream_t)stream);
-        (void)hipFree(tmp);
+    char *base = static_cast<char *>(in->ptr_block);
+    in->cptr = reinterpret_cast<int *>(base);
+    in->cidx = reinterpret_cast<uint32_t *>(base + L.idx_at);
+    in->xval = reinterpret_cast<float *>(base + L.val_at);
+    s = emit_run(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, relu, y_dev, stream, in);
+    if (s != FSCNN_OK) {
+        (void)hipStreamSynchronize((hipStream_t)stream);   // nothing may still write into what is freed next
+        (void)hipEventDestroy(in->filled);
+        (void)hipFree(in->ptr_block);
+        in->magic = 0;
+        delete in;
+        return s;
     }
-    return s;
+    *out = in;
+    return FSCNN_OK;
+}
+
+fscnn_status_t fscnn_conv2d_sparse_filter_emit_into(fscnn_filter_t *f, const float *x_dev, int N,
+                                                    int C, int H, int W, int sh, int sw, int ph,
+                                                    int pw, const float *bias_dev, int relu,
+                                                    float *y_dev, void *stream, fscnn_input_t *into)
+{
+    if (!f || !x_dev || !into) return FSCNN_ERR_NULL;
+    if (!live(into)) return FSCNN_ERR_HANDLE;
+    int Ho, Wo, NCH;
+    fscnn_status_t s = emit_check(f, N, C, H, W, sh, sw, ph, pw, &Ho, &Wo, &NCH);
+    if (s != FSCNN_OK) return s;
+    int dev;
+    s = have_device(&dev);
+    if (s != FSCNN_OK) return s;
+    if (into->device != dev) return FSCNN_ERR_MISMATCH;
+    // only a handle that an emitting call made, for a result of this very shape, has the room
+    if (into->emit_bytes == 0) return FSCNN_ERR_UNSUPPORTED;
+    if (into->N != N || into->C != f->K || into->H != Ho || into->W != Wo) return FSCNN_ERR_MISMATCH;
+    if (!y_dev && !into->emit_has_y) return FSCNN_ERR_NULL;
+    return emit_run(f, x_dev, N, C, H, W, sh, sw, ph, pw, bias_dev, relu, y_dev, stream, into);
 }
 
 fscnn_status_t fscnn_input_info(const fscnn_input_t *in, int *N, int *C, int *H, int *W,
@@ -663,7 +795,10 @@ fscnn_status_t fscnn_input_info(const fscnn_input_t *in, int *N, int *C, int *H,
     if (C) *C = in->C;
     if (H) *H = in->H;
     if (W) *W = in->W;
-    if (nnz) *nnz = in->nnz;
+    if (nnz) {
+        *nnz = input_nnz(in);
+        if (*nnz < 0) return FSCNN_ERR_DEVICE;
+    }
     return FSCNN_OK;
 }
 
@@ -672,16 +807,18 @@ fscnn_status_t fscnn_input_export(const fscnn_input_t *in, int *prow_host, unsig
 {
     if (!in || !prow_host) return FSCNN_ERR_NULL;
     if (!live(in)) return FSCNN_ERR_HANDLE;
-    if (in->nnz > 0 && (!cidx_host || !val_host)) return FSCNN_ERR_NULL;
+    const long long stored = input_nnz(in);
+    if (stored < 0) return FSCNN_ERR_DEVICE;
+    if (stored > 0 && (!cidx_host || !val_host)) return FSCNN_ERR_NULL;
     FSCNN_HIP(hipEventSynchronize(in->filled));
     // the row pointers are every NCH-th chunk pointer
     const size_t npix = (size_t)in->N * in->H * in->W;
     FSCNN_HIP(hipMemcpy2D(prow_host, sizeof(int), in->cptr, sizeof(int) * (size_t)in->NCH, sizeof(int), npix,
                           hipMemcpyDeviceToHost));
     FSCNN_HIP(hipMemcpy(prow_host + npix, in->cptr + npix * (size_t)in->NCH, sizeof(int), hipMemcpyDeviceToHost));
-    if (in->nnz > 0) {
-        FSCNN_HIP(hipMemcpy(cidx_host, in->cidx, sizeof(uint32_t) * (size_t)in->nnz, hipMemcpyDeviceToHost));
-        FSCNN_HIP(hipMemcpy(val_host, in->xval, sizeof(float) * (size_t)in->nnz, hipMemcpyDeviceToHost));
+    if (stored > 0) {
+        FSCNN_HIP(hipMemcpy(cidx_host, in->cidx, sizeof(uint32_t) * (size_t)stored, hipMemcpyDeviceToHost));
+        FSCNN_HIP(hipMemcpy(val_host, in->xval, sizeof(float) * (size_t)stored, hipMemcpyDeviceToHost));
     }
     return FSCNN_OK;
 }

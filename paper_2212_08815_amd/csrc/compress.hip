@@ -297,13 +297,14 @@ __global__ void __launch_bounds__(kBlock) input_fill_kernel(const float *__restr
                                                             int NCH, int PX,
                                                             const int *__restrict__ cptr,
                                                             uint32_t *__restrict__ cidx,
-                                                            float *__restrict__ xval, long long total,
-                                                            int spare)
+                                                            float *__restrict__ xval, int spare)
 {
     extern __shared__ uint32_t stage[];   // [cap] channel indices, then [cap] value bit patterns
     const int cap = PX * NCH * CC;
-    // the entries past the last stored one (readers fetch a few positions ahead)
+    // the entries past the last stored one (readers fetch a few positions ahead); the number of
+    // stored entries is the pointer array's last element
     if (blockIdx.x == 0 && (int)threadIdx.x < spare) {
+        const long long total = cptr[npix * NCH];
         cidx[total + threadIdx.x] = 0u;
         xval[total + threadIdx.x] = 0.0f;
     }
@@ -466,8 +467,7 @@ hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int CC
 }
 
 hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, int CC, int NCH,
-                             const int *cptr, uint32_t *cidx, float *xval, long long total, int spare,
-                             hipStream_t st)
+                             const int *cptr, uint32_t *cidx, float *xval, int spare, hipStream_t st)
 {
     const long long HW = (long long)H * W, npix = (long long)N * HW;
     if (spare > kBlock) return hipErrorInvalidValue;
@@ -478,7 +478,7 @@ hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, int CC,
     const long long lds = (long long)PX * NCH * CC * 8;
     if (lds > 65536) return hipErrorInvalidValue;   // more than 8192 channels: not served
     hipLaunchKernelGGL(input_fill_kernel, dim3(blocks_for(npix, PX)), dim3(kBlock), (size_t)lds, st, x, C,
-                       HW, npix, CC, NCH, PX, cptr, cidx, xval, total, spare);
+                       HW, npix, CC, NCH, PX, cptr, cidx, xval, spare);
     return hipGetLastError();
 }
 

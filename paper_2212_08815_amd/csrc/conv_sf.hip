@@ -157,7 +157,8 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                      const float *__restrict__ bias, const Rec *__restrict__ recs,
                      const int *__restrict__ segptr, int N, int C, int H, int W, int K, int Ho,
                      int Wo, int ph, int pw, int relu, int NCH, int NG, int tiles_x,
-                     int tiles_per_img, int nblk, int csplit, long long part_stride)
+                     int tiles_per_img, int nblk, int csplit, long long part_stride,
+                     int *__restrict__ emit_cnt)
 {
     using V = typename VecT<G::BV>::T;
     extern __shared__ __align__(256) char ldsb[];
@@ -536,8 +537,61 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                         float r = acc[j][v * G::BV + b] + bk;
                         r = act_apply(r, relu);
                         yk[(long long)oy * Wo + ox] = r;
+                        // sparse output: remember in the accumulator, now dead, whether this result counts
+                        acc[j][v * G::BV + b] = r != 0.0f ? 1.0f : 0.0f;
+                    } else {
+                        acc[j][v * G::BV + b] = 0.0f;
                     }
                 }
+            }
+        }
+    }
+    // ---- sparse output emission (Sec. 4, the sparse-output remark of "Sparse Tensor Convolution"):
+    // per output pixel and step of 8 output channels, the number of non-zero results -- what the
+    // activation compressor counts in a pass of its own over a dense tensor.  A step's 8 channels
+    // belong to 8 / SLOTS waves of this work-group: every wave drops its per-pixel counts into LDS
+    // (free by now), then one thread per (step, pixel) adds them and stores the sum.  One writer per
+    // count, no atomics.
+    if constexpr (!G::OUT4) {
+        if (emit_cnt != nullptr && csplit == 1) {
+            static_assert(8 % G::SLOTS == 0 || G::SLOTS % 8 == 0, "channel steps of 8 align with the waves' slots");
+            unsigned char *lc = reinterpret_cast<unsigned char *>(ldsb);   // [wave][pixel slot p][lane]
+            static_assert(G::WAVES * G::P * 64 <= G::LDS_BYTES, "per-wave counts fit the tile's LDS");
+            __syncthreads();   // every wave has left the chunk loop (the tile buffers are free)
+            constexpr int SPW = G::SLOTS >= 8 ? G::SLOTS / 8 : 1;   // steps per wave
+            constexpr int WPS = G::SLOTS >= 8 ? 1 : 8 / G::SLOTS;   // waves per step
+#pragma unroll
+            for (int q = 0; q < SPW; ++q)
+#pragma unroll
+                for (int p = 0; p < G::P; ++p) {
+                    float c = 0.0f;
+#pragma unroll
+                    for (int j = q * (G::SLOTS / SPW); j < (q + 1) * (G::SLOTS / SPW); ++j)
+                        if (kg * G::KG + wave * G::SLOTS + j < K) c += acc[j][p];
+                    lc[((wave * SPW + q) * G::P + p) * 64 + lane] = (unsigned char)(int)c;
+                }
+            __syncthreads();
+            const int NCH8 = (K + 7) / 8;
+            constexpr int STEPS = G::KG / 8;   // steps of 8 channels this work-group owns
+            static_assert(G::KG % 8 == 0, "a work-group owns whole steps");
+            for (int t = tid; t < STEPS * G::P * 64; t += G::NT) {
+                const int ln = t % 64, p = (t / 64) % G::P, st = t / (64 * G::P);
+                int c = 0;
+                if constexpr (G::SLOTS >= 8) {
+                    c = lc[(((st / SPW) * SPW + st % SPW) * G::P + p) * 64 + ln];
+                } else {
+#pragma unroll
+                    for (int u = 0; u < WPS; ++u) c += lc[((st * WPS + u) * G::P + p) * 64 + ln];
+                }
+                // pixel of (lane ln, accumulator p): the epilogue's own mapping
+                const int plx = ln % G::LW, plg = (ln / G::LW) % G::LHR;
+                const int plh = (G::LW == 16 && G::LHR == 4) ? (((plg & 1) << 1) | (plg >> 1)) : plg;
+                const int pig = ln / (G::LW * G::LHR);
+                const int v = p / G::BV, b = p % G::BV;
+                const int n = n0 + pig * G::BV + b, oy = ty0 + plh * G::NV + v, ox2 = tx0 + plx;
+                const int step = kg * STEPS + st;
+                if (n < N && oy < Ho && ox2 < Wo && step < NCH8)
+                    emit_cnt[(((long long)n * Ho + oy) * Wo + ox2) * NCH8 + step] = c;
             }
         }
     }
@@ -597,12 +651,12 @@ __global__ void __launch_bounds__(256) split_sum_kernel(const float *__restrict_
 
 // ---------------------------------------------------------------- variant table
 using LaunchFn = hipError_t (*)(const SfPlan &, const float *, int, int, int, int, int, int, int,
-                                int, int, const float *, int, float *, int, long long, hipStream_t);
+                                int, int, const float *, int, float *, int, long long, int *, hipStream_t);
 
 template <class G>
 hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K, int Ho,
                         int Wo, int ph, int pw, const float *bias, int relu, float *y, int csplit,
-                        long long part_stride, hipStream_t st)
+                        long long part_stride, int *emit_cnt, hipStream_t st)
 {
     static_assert(G::LDS_BYTES <= 160 * 1024, "tile exceeds the 160 KB LDS of a gfx950 CU");
     if (G::LDS_BYTES > 64 * 1024) {
@@ -619,7 +673,7 @@ hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, in
     if (nblk <= 0 || nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(conv_sf_tiled_kernel<G>, dim3((unsigned)nblk), dim3(G::NT), G::LDS_BYTES, st,
                        x, y, bias, p.recs, p.segptr, N, C, H, W, K, Ho, Wo, ph, pw, relu, p.NCH,
-                       p.NG, tiles_x, tiles_x * tiles_y, (int)nblk, csplit, part_stride);
+                       p.NG, tiles_x, tiles_x * tiles_y, (int)nblk, csplit, part_stride, emit_cnt);
     return hipGetLastError();
 }
 
@@ -875,7 +929,7 @@ long long sf_split_elems(int N, int K, int Ho, int Wo, int out4)
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
                                 float *y, int in4, int out4, int pool, int csplit, float *parts,
-                                hipStream_t st)
+                                int *emit_cnt, hipStream_t st)
 {
     int n;
     const Variant *t = variants(&n);
@@ -888,13 +942,15 @@ hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, i
         // sf_split_elems floats of scratch), then one pass adds the copies, bias and activation
         if (!parts) return hipErrorInvalidValue;
         const long long total = sf_split_elems(N, K, Ho, Wo, out4);
-        hipError_t e = fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, parts, csplit, total, st);
+        if (emit_cnt) return hipErrorInvalidValue;   // the parts' sums are not final results
+        hipError_t e = fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, parts, csplit, total, nullptr, st);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, parts,
                            csplit, total, bias, K, (long long)Ho * Wo, out4 ? 4 : 1, relu, total, y);
         return hipGetLastError();
     }
-    return fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, 1, 0, st);
+    if (emit_cnt && (out4 || pool)) return hipErrorInvalidValue;
+    return fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, 1, 0, emit_cnt, st);
 }
 
 // How many ways the input channels are split for a launch: small problems (deep layers at small

@@ -104,7 +104,8 @@ struct fscnn_input {
     uint64_t magic;
     int device;
     int N, C, H, W;
-    long long nnz;
+    long long nnz;   // -1: not fetched yet (the handle was filled without a host synchronisation;
+                     // input_nnz() waits for `filled` and reads cptr's last element)
     int CC, NCH;     // chunking of the channel axis used by cptr
     uint32_t *cidx;  // device [nnz]
     float *xval;     // device [nnz]
@@ -113,6 +114,10 @@ struct fscnn_input {
     // the two device allocations behind the arrays: pointers (and the counts they were scanned
     // from), then indices and values
     void *ptr_block, *node_block;
+    // a handle made by an emitting convolution has ONE allocation (ptr_block) of emit_bytes, sized
+    // for the worst case, with room for the dense result iff emit_has_y; 0 for other handles
+    size_t emit_bytes = 0;
+    bool emit_has_y = false;
     // the pass that fills the handle runs on `made_on` and may still be in flight when the
     // handle is returned; `filled` is recorded behind it, for users on other streams
     hipStream_t made_on;
@@ -144,10 +149,9 @@ hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float 
                             hipStream_t st);
 hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int CC, int NCH, int *cnt,
                               hipStream_t st);
-// also zeroes the `spare` entries that follow the last stored one
+// also zeroes the `spare` entries that follow the last stored one (cptr's last element says where)
 hipError_t launch_input_fill(const float *x, int N, int C, int H, int W, int CC, int NCH,
-                             const int *cptr, uint32_t *cidx, float *xval, long long total, int spare,
-                             hipStream_t st);
+                             const int *cptr, uint32_t *cidx, float *xval, int spare, hipStream_t st);
 hipError_t launch_maxpool2x2(const float *x, int N, int C, int H, int W, float *y, int n4,
                              hipStream_t st);
 hipError_t launch_layout_convert(const float *src, int N, int C, int H, int W, int src_n4, float *dst,
@@ -162,10 +166,13 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int strid
 bool sf_variant_has_layout(int variant, int in4, int out4, int pool);
 // csplit > 1: `parts` is scratch of csplit * sf_split_elems(...) floats (one copy of y per part)
 long long sf_split_elems(int N, int K, int Ho, int Wo, int out4);
+// emit_cnt != nullptr (NCHW output, no pool, csplit == 1 only): the epilogue also stores, per output
+// pixel p = (n*Ho + oy)*Wo + ox and step j of 8 output channels, the number of non-zero results into
+// emit_cnt[p * ceil(K/8) + j] -- the counts the activation compressor scans
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
                                 float *y, int in4, int out4, int pool, int csplit, float *parts,
-                                hipStream_t st);
+                                int *emit_cnt, hipStream_t st);
 // 1, or the number of parts the input-channel range is split into for a small problem
 int sf_choose_csplit(int variant, int N, int K, int Ho, int Wo, int NCH);
 hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const float *val,

@@ -26,6 +26,7 @@ EXPORTS = [
     "fscnn_filter_destroy", "fscnn_sf_variant_count", "fscnn_sf_variant_name", "fscnn_sf_variant_choice",
     "fscnn_conv2d_sparse_filter", "fscnn_conv2d_sparse_filter_v", "fscnn_input_compress",
     "fscnn_conv2d_sparse_filter_emit",
+    "fscnn_conv2d_sparse_filter_emit_into",
     "fscnn_input_info", "fscnn_input_export", "fscnn_input_destroy", "fscnn_conv2d_sparse_input",
     "fscnn_maxpool2x2", "fscnn_conv2d_sparse_filter_ex", "fscnn_layout_convert",
     "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2", "fscnn_probe_gather_fma",
@@ -274,12 +275,21 @@ def layout_convert(x, src_layout, n=None):
 
 
 class SparseInput:
-    """Owner of a fscnn_input_t handle."""
+    """Owner of a fscnn_input_t handle.  `nnz` is asked of the library on first use (for a handle
+    that a convolution emitted this waits for the pass that fills it)."""
 
-    def __init__(self, handle, shape, nnz):
+    def __init__(self, handle, shape, nnz=None):
         self._h = handle
         self.shape = shape
-        self.nnz = nnz
+        self._nnz = nnz
+
+    @property
+    def nnz(self):
+        if self._nnz is None:
+            n = ctypes.c_longlong()
+            _check(lib().fscnn_input_info(self.handle, None, None, None, None, ctypes.byref(n)), "fscnn_input_info")
+            self._nnz = n.value
+        return self._nnz
 
     def __del__(self):
         try:
@@ -313,9 +323,12 @@ def input_compress(x):
     return SparseInput(h, (N, C, H, W), nnz.value)
 
 
-def conv2d_sparse_filter_emit(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=False, dense_out=None):
+def conv2d_sparse_filter_emit(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=False, dense_out=None,
+                              into=None):
     """fscnn_conv2d_sparse_filter_emit: NCHW x -> SparseInput holding the non-zero results of the
-    convolution.  dense_out, if given (N x K x Ho x Wo), also receives the dense result."""
+    convolution.  dense_out, if given (N x K x Ho x Wo), also receives the dense result.  into, a
+    SparseInput that an earlier call returned for the same shapes, is refilled and returned
+    (fscnn_conv2d_sparse_filter_emit_into: no allocation)."""
     x = _dev_f32(x, "x")
     bias = _dev_f32(bias, "bias")
     if x.dim() != 4:
@@ -329,14 +342,19 @@ def conv2d_sparse_filter_emit(f, x, stride=(1, 1), pad=(0, 0), bias=None, relu=F
             raise TypeError("dense_out has the wrong shape")
     if bias is not None and bias.numel() != K:
         raise TypeError("bias must have K entries")
+    if into is not None:
+        _check(lib().fscnn_conv2d_sparse_filter_emit_into(
+            f.handle, _ptr(x), _i(N), _i(C), _i(H), _i(W), _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]),
+            _ptr(bias), _i(bool(relu)), _ptr(dense_out), _stream(), into.handle),
+            "fscnn_conv2d_sparse_filter_emit_into")
+        into._nnz = None
+        return into
     h = ctypes.c_void_p()
     _check(lib().fscnn_conv2d_sparse_filter_emit(
         f.handle, _ptr(x), _i(N), _i(C), _i(H), _i(W), _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]),
         _ptr(bias), _i(bool(relu)), _ptr(dense_out), _stream(), ctypes.byref(h)),
         "fscnn_conv2d_sparse_filter_emit")
-    nnz = ctypes.c_longlong()
-    _check(lib().fscnn_input_info(h, None, None, None, None, ctypes.byref(nnz)), "fscnn_input_info")
-    return SparseInput(h, (N, K, Ho, Wo), nnz.value)
+    return SparseInput(h, (N, K, Ho, Wo))
 
 
 def input_export(s):

@@ -51,6 +51,8 @@ CASES = [
     (2, 24, 16, 17, 15, 3, 3, (2, 2), (1, 1)),      # stride 2
     (1, 33, 20, 9, 12, 1, 1, (1, 1), (0, 0)),       # 1x1 filters
     (1, 7, 66, 10, 9, 5, 2, (1, 2), (2, 0)),        # direct kernel
+    (16, 72, 96, 56, 56, 3, 3, (1, 1), (1, 1)),     # many chunks and enough work-groups not to split: epilogue counts
+    (1, 128, 40, 14, 14, 3, 3, (1, 1), (1, 1)),     # small and deep: channel-split mode, counted in a separate pass
 ]
 
 
@@ -110,6 +112,41 @@ def test_emit_chains_into_the_sparse_input_convolution(F):
     m = densify(*F.input_export(mid), o1.shape)
     o3, a3 = oracle.conv2d_dense(m, w2, (1, 1), (1, 1), b2, True, want_abs=True)
     assert_parity(g, o3, a3, 40 * 9, "sparse input on the emitted tensor")
+
+
+def test_emit_into_refills_a_handle_without_allocating(F):
+    n, c, k, h, w_ = 5, 24, 37, 19, 21
+    x1, w, b = inputs.random_layer(520, n, c, k, h, w_, 3, 3, keep=0.3)
+    x2 = inputs.random_layer(521, n, c, k, h, w_, 3, 3, keep=0.3)[0]
+    f = F.filter_compress(dev(w))
+    s = F.conv2d_sparse_filter_emit(f, dev(x1), (1, 1), (1, 1), dev(b), True)
+    first = F.input_export(s)
+    for x in (x2, x1):                       # other contents (another count of non-zeros), then back
+        fresh = F.input_export(F.conv2d_sparse_filter_emit(f, dev(x), (1, 1), (1, 1), dev(b), True))
+        free0 = torch.cuda.mem_get_info()[0]
+        again = F.conv2d_sparse_filter_emit(f, dev(x), (1, 1), (1, 1), dev(b), True, into=s)
+        assert again is s and torch.cuda.mem_get_info()[0] == free0
+        got = F.input_export(s)
+        assert s.nnz == fresh[0][-1]
+        assert all(np.array_equal(bits(g) if g.dtype == np.float32 else g,
+                                  bits(e) if e.dtype == np.float32 else e) for g, e in zip(got, fresh))
+    assert all(np.array_equal(g, e) for g, e in zip(got, first))
+    yd = torch.empty((n, k, h, w_), dtype=torch.float32, device="cuda")
+    F.conv2d_sparse_filter_emit(f, dev(x2), (1, 1), (1, 1), dev(b), True, dense_out=yd, into=s)
+    op, oc, ov = oracle.input_compress(host(yd))
+    prow, cidx, val = F.input_export(s)
+    assert np.array_equal(prow, op) and np.array_equal(cidx, oc) and np.array_equal(bits(val), bits(ov))
+    # a handle of another shape or origin is refused; one made with a dense_out has no room for y
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_filter_emit(f, dev(x1[:4]), (1, 1), (1, 1), dev(b), True, into=s)
+    assert e.value.status == 3
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_filter_emit(f, dev(x1), (1, 1), (1, 1), dev(b), True, into=F.input_compress(yd))
+    assert e.value.status == 4
+    s3 = F.conv2d_sparse_filter_emit(f, dev(x1), (1, 1), (1, 1), dev(b), True, dense_out=yd)
+    with pytest.raises(F.FscnnError) as e:
+        F.conv2d_sparse_filter_emit(f, dev(x1), (1, 1), (1, 1), dev(b), True, into=s3)
+    assert e.value.status == 1
 
 
 def test_emit_nothing_and_everything(F):
