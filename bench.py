@@ -154,6 +154,30 @@ def rel_err(np, g, o):
     return float(np.max(np.abs(g - o) / np.maximum(np.abs(o), tau if tau > 0 else 1.0)))
 
 
+def probe_gather_fma(torch, iters=20000, work_groups=2048):
+    """TFLOP/s the chip sustains on the hot loop's instruction mix (one LDS word per fused
+    multiply-add) without sparsity, staging or barriers: the kernel of libfscnn_bench_probe.so, a
+    shared object of this script's own (the library does not hold it), timed with HIP events."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2212_08815_amd", "libfscnn_bench_probe.so")
+    if not os.path.exists(path):
+        from paper_2212_08815_amd import build
+        build.build()
+    probe = ctypes.CDLL(path).bench_probe_gather_fma
+    probe.restype = ctypes.c_int
+    probe.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    scratch = torch.ones(4, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    assert probe(scratch.data_ptr(), 100, work_groups, stream) == 0
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    assert probe(scratch.data_ptr(), iters, work_groups, stream) == 0
+    b.record()
+    torch.cuda.synchronize()
+    return work_groups * 256.0 * iters * 32.0 / (a.elapsed_time(b) * 1e-3) / 1e12
+
+
 def time_gpu(torch, fn, iters):
     """Average milliseconds of fn() over `iters` calls (HIP events on the current stream)."""
     fn()
@@ -443,7 +467,7 @@ def main():
     dom_tflops = dom_flop / (dom_ms * 1e-3) / 1e12
     lay = {fscnn.NCHW: "NCHW", fscnn.N4: "N4"}
     roofline = dict(bound="alu", achieved=dom_tflops, peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s",
-                    frac=dom_tflops / FP32_VECTOR_PEAK_TFLOPS, traffic=None,
+                    frac=dom_tflops / FP32_VECTOR_PEAK_TFLOPS, traffic=None, traffic_source=None,
                     kernel="conv_sf_tiled_kernel %s %s->%s%s, layers %s" % (
                         dom_id[0], lay[dom_id[1]], lay[dom_id[2]], " +pool" if dom_id[3] else "",
                         ",".join(str(li + 1) for li in dom)),
@@ -455,18 +479,24 @@ def main():
     # measured HBM bytes of that launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy
     # kernel of known size): taken from the committed summary of the same workload, else null
     # what the chip sustains on the hot loop's instruction mix alone (one LDS word per FMA)
-    ceiling = fscnn.probe_gather_fma()
+    ceiling = probe_gather_fma(torch)
     roofline["measured_gather_fma_ceiling"] = ceiling
     roofline["frac_of_measured_ceiling"] = dom_tflops / ceiling
     traffic_file = os.path.join(ROOT, "profiles", "conv_sf_vgg16_n32_hbm_traffic.txt")
     if os.path.exists(traffic_file) and n == 32 and abs(args.keep - 0.05) < 1e-9:
         per_layer = {}
+        measured_at = None
         for line in open(traffic_file):
             f = line.split()
             if len(f) == 4 and f[0].startswith("layer_"):
                 per_layer[int(f[0][6:]) - 1] = float(f[3])
+            elif len(f) >= 2 and f[0] == "commit:":
+                measured_at = f[1]
         if all(li in per_layer for li in dom):
             roofline["traffic"] = float(np.mean([per_layer[li] for li in dom]))
+            # not measured by this run: read from the committed counter summary, which names the
+            # commit whose kernels the counters were collected on
+            roofline["traffic_source"] = dict(file=os.path.relpath(traffic_file, ROOT), commit=measured_at)
 
     out = dict(
         metric="effective GFLOP/s (2*nnz*Ho*Wo*N) + HBM GB/s fraction, VGG16-shaped stack @95%",

@@ -351,14 +351,6 @@ fscnn_status_t fscnn_sparse_tensor_transpose(const int *rowptr_dev, const unsign
  * Host-only. */
 long long fscnn_sparse_transpose_workspace(long long new_rows, long long nnz);
 
-/* Measurement helper (no counterpart in the paper): launches `work_groups` groups of 256 threads
- * that each repeat, `iters` times, the instruction mix of the convolution's hot loop on a
- * resident LDS tile -- 1 address add, 4 conflict-free ds_read_b128 (16 words per lane), 16 FMAs
- * with a scalar weight -- with no sparsity, staging or barriers.  The caller times it; the
- * flop count is work_groups * 256 * iters * 32.  scratch_dev: at least 2 floats, the first one
- * is read as the weight.  Asynchronous on `stream`. */
-fscnn_status_t fscnn_probe_gather_fma(float *scratch_dev, int iters, int work_groups, void *stream);
-
 #ifdef __cplusplus
 }
 #endif

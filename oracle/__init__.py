@@ -20,13 +20,19 @@ _lib = None
 
 
 def build(force=False):
-    """Compile the oracle with gcc (-O2, OpenMP, no intrinsics)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
-                               "-o", tmp, _SRC, "-lm"])
-        os.replace(tmp, _LIB)
-    return _LIB
+    """Compile the oracle with gcc (-O2, OpenMP, no intrinsics).  With FSCNN_ORACLE_SANITIZE=1 in
+    the environment a copy instrumented with -fsanitize=address,undefined is built and loaded
+    instead (the process then needs gcc's libasan.so preloaded: see tests/README_sanitize.txt)."""
+    san = os.environ.get("FSCNN_ORACLE_SANITIZE") == "1"
+    lib = _LIB.replace(".so", "_asan.so") if san else _LIB
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        tmp = lib + ".tmp%d" % os.getpid()
+        flags = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                 "-fno-sanitize-recover=undefined"] if san else ["-O2"]
+        subprocess.check_call(["gcc"] + flags + ["-std=c99", "-fopenmp", "-fPIC", "-shared",
+                                                 "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, lib)
+    return lib
 
 
 _f32p = ctypes.POINTER(ctypes.c_float)

@@ -1,4 +1,5 @@
-"""Builds libfscnn.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
+"""Builds libfscnn.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree, and beside it
+libfscnn_bench_probe.so, the measurement helper that only bench.py loads.
 
     python -m paper_2212_08815_amd.build [--force]
 
@@ -16,6 +17,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libfscnn.so")
 SOURCES = ["api.hip", "compress.hip", "conv_sf.hip", "conv_si.hip", "transpose.hip"]
+PROBE_LIB = os.path.join(HERE, "libfscnn_bench_probe.so")
+PROBE_SRC = os.path.join(CSRC, "bench_probe.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          # packed-fp32 forms are switched off for every device function of the library
@@ -62,6 +65,13 @@ def build(force=False, extra_flags=(), verbose=True):
         tmp = LIB + ".tmp%d" % os.getpid()
         subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs)
         os.replace(tmp, LIB)
+    if force or not _newer(PROBE_LIB, [PROBE_SRC, os.path.abspath(__file__)]):
+        tmp = PROBE_LIB + ".tmp%d" % os.getpid()
+        r = subprocess.run([HIPCC] + FLAGS + ["-shared", "-o", tmp, PROBE_SRC], capture_output=True, text=True)
+        if r.returncode != 0:
+            print(r.stdout + r.stderr)
+            raise RuntimeError("hipcc failed on %s" % PROBE_SRC)
+        os.replace(tmp, PROBE_LIB)
     return LIB
 
 

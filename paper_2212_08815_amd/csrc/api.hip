@@ -990,17 +990,6 @@ fscnn_status_t fscnn_sparse_tensor_transpose(const int *rowptr_dev, const unsign
                           tptr_dev, cidx_dev, tval_dev, workspace_dev, workspace_bytes, stream);
 }
 
-fscnn_status_t fscnn_probe_gather_fma(float *scratch_dev, int iters, int work_groups, void *stream)
-{
-    if (!scratch_dev) return FSCNN_ERR_NULL;
-    if (iters <= 0 || work_groups <= 0 || work_groups > (1 << 20)) return FSCNN_ERR_SHAPE;
-    int dev;
-    fscnn_status_t s = have_device(&dev);
-    if (s != FSCNN_OK) return s;
-    FSCNN_HIP(run_gather_fma_probe(scratch_dev, iters, work_groups, (hipStream_t)stream));
-    return FSCNN_OK;
-}
-
 fscnn_status_t fscnn_maxpool2x2_ex(const float *x_dev, int N, int C, int H, int W, float *y_dev,
                                    fscnn_layout_t layout, void *stream)
 {

@@ -986,48 +986,3 @@ hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const f
 }
 
 }  // namespace fscnn
-
-// ---------------------------------------------------------------- measurement helper
-// Ceiling probe for the hot loop's instruction mix, with no sparsity, staging or barriers: every
-// wave repeats {1 address add, 4 x ds_read_b128 (conflict-free, 16 words per lane), 16 FMAs with a
-// scalar weight} at full occupancy.  What it reports is the rate at which gfx950 sustains one LDS
-// word per fused multiply-add; bench.py prints it beside the kernel's achieved rate.
-namespace fscnn {
-namespace {
-__global__ void __launch_bounds__(256) gather_fma_probe_kernel(float *out, int iters)
-{
-    __shared__ __align__(16) float tile[8192];  // 32 KB
-    for (int i = threadIdx.x; i < 8192; i += 256) tile[i] = 1.0f + i * 1e-6f;
-    __syncthreads();
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const char *base = reinterpret_cast<const char *>(tile) + lane * 16 + wave * 2048;
-    float acc[16];
-#pragma unroll
-    for (int p = 0; p < 16; ++p) acc[p] = 0.0f;
-    const float w = out[0];
-    for (int it = 0; it < iters; ++it) {
-        const char *p = base + ((it & 7) << 8);  // stays inside the tile: < 8 KB + 2 KB + 4 x 1 KB + 1 KB
-        float4 in[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) in[v] = *reinterpret_cast<const float4 *>(p + v * 1056);
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            acc[v * 4 + 0] = __builtin_fmaf(w, in[v].x, acc[v * 4 + 0]);
-            acc[v * 4 + 1] = __builtin_fmaf(w, in[v].y, acc[v * 4 + 1]);
-            acc[v * 4 + 2] = __builtin_fmaf(w, in[v].z, acc[v * 4 + 2]);
-            acc[v * 4 + 3] = __builtin_fmaf(w, in[v].w, acc[v * 4 + 3]);
-        }
-    }
-    float s = 0.0f;
-#pragma unroll
-    for (int p = 0; p < 16; ++p) s += acc[p];
-    if (s == 123.456f) out[1] = s;  // keeps the loop alive; never true for the values used
-}
-}  // namespace
-
-hipError_t run_gather_fma_probe(float *scratch_dev, int iters, int blocks, hipStream_t st)
-{
-    hipLaunchKernelGGL(gather_fma_probe_kernel, dim3(blocks), dim3(256), 0, st, scratch_dev, iters);
-    return hipGetLastError();
-}
-}  // namespace fscnn

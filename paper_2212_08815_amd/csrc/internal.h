@@ -180,8 +180,6 @@ hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const f
                                  int Ho, int Wo, int sh, int sw, int ph, int pw, const float *bias,
                                  int relu, float *y, hipStream_t st);
 
-hipError_t run_gather_fma_probe(float *scratch_dev, int iters, int blocks, hipStream_t st);
-
 // ---- transpose.hip
 long long reorder_workspace_bytes(long long n_buckets, long long nnz);  // -1: too large
 // Size of the per-GPU static scratch of fscnn_sparse_transpose_noalloc, and its device address on

@@ -29,7 +29,7 @@ EXPORTS = [
     "fscnn_conv2d_sparse_filter_emit_into",
     "fscnn_input_info", "fscnn_input_export", "fscnn_input_destroy", "fscnn_conv2d_sparse_input",
     "fscnn_maxpool2x2", "fscnn_conv2d_sparse_filter_ex", "fscnn_layout_convert",
-    "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2", "fscnn_probe_gather_fma",
+    "fscnn_maxpool2x2_ex", "fscnn_conv2d_sparse_filter_pool2x2",
     "fscnn_sparse_transpose", "fscnn_sparse_tensor_transpose", "fscnn_sparse_transpose_workspace",
     "fscnn_dense_filter_prepare", "fscnn_dense_filter_destroy", "fscnn_conv2d_sparse_input_prepared",
     "fscnn_si_variant_count", "fscnn_conv2d_sparse_filter_leaky", "fscnn_sparse_transpose_noalloc",
@@ -515,17 +515,3 @@ def sparse_tensor_transpose(rowptr, widx, val, W, H, C, workspace=None):
     if rowptr.numel() != C * H + 1:
         raise TypeError("rowptr must have C*H + 1 elements")
     return _transpose("fscnn_sparse_tensor_transpose", rowptr, widx, val, (W, H, C), W * H, workspace)
-
-
-def probe_gather_fma(iters=20000, work_groups=2048):
-    """fscnn_probe_gather_fma timed with HIP events: TFLOP/s the chip sustains on the hot loop's
-    instruction mix (one LDS word per fused multiply-add) without sparsity, staging or barriers."""
-    scratch = torch.ones(4, dtype=torch.float32, device="cuda")
-    _check(lib().fscnn_probe_gather_fma(_ptr(scratch), _i(100), _i(work_groups), _stream()), "fscnn_probe_gather_fma")
-    torch.cuda.synchronize()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    _check(lib().fscnn_probe_gather_fma(_ptr(scratch), _i(iters), _i(work_groups), _stream()), "fscnn_probe_gather_fma")
-    b.record()
-    torch.cuda.synchronize()
-    return work_groups * 256.0 * iters * 32.0 / (a.elapsed_time(b) * 1e-3) / 1e12
