@@ -35,8 +35,8 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector peak (counts pac
 FP32_UNPACKED_PEAK_TFLOPS = 78.6  # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz, one FMA/lane/clk
 
 
-def build_stack(fscnn, torch, inputs, n, keep):
-    x, layers = inputs.vgg16_stack(4, n, keep)
+def build_stack(fscnn, torch, inputs, n, keep, config_id=4):
+    x, layers = inputs.vgg16_stack(config_id, n, keep)
     dev_layers = []
     t0 = time.perf_counter()
     for L in layers:
@@ -54,21 +54,26 @@ def build_stack(fscnn, torch, inputs, n, keep):
     return torch.from_numpy(x).cuda(), dev_layers, compress_ms
 
 
-def alloc_buffers(fscnn, torch, dev_layers, n, fuse_pool):
-    """Output tensors of every layer (and pool), allocated once: the timed loop allocates nothing."""
+def alloc_buffers(fscnn, torch, dev_layers, n, fuse_pool, n4=True):
+    """Output tensors of every layer (and pool), allocated once: the timed loop allocates nothing.
+    n4: tensors between the layers in the image-interleaved layout (batches of at least four);
+    else NCHW throughout, and a pool is merged only where the automatic choice has a pooled form."""
     last = len(dev_layers) - 1
     for li, d in enumerate(dev_layers):
         hw = d["hw"]
-        lay_out = fscnn.NCHW if li == last else fscnn.N4
-        shape = (n, d["k"], hw, hw) if lay_out == fscnn.NCHW else fscnn.n4_shape(n, d["k"], hw, hw)
-        d["y"] = torch.empty(shape, dtype=torch.float32, device="cuda")
-        d["lay_in"] = fscnn.NCHW if li == 0 else fscnn.N4
+        lay_out = fscnn.NCHW if li == last or not n4 else fscnn.N4
+        shape = lambda h: (n, d["k"], h, h) if lay_out == fscnn.NCHW else fscnn.n4_shape(n, d["k"], h, h)
+        d["y"] = torch.empty(shape(hw), dtype=torch.float32, device="cuda")
+        d["lay_in"] = fscnn.NCHW if li == 0 or not n4 else fscnn.N4
         d["lay_out"] = lay_out
-        if d["pool"] and fuse_pool:            # the conv launch stores the pooled tensor only
-            d["y"] = torch.empty(fscnn.n4_shape(n, d["k"], hw // 2, hw // 2), dtype=torch.float32, device="cuda")
+        fused = bool(d["pool"] and fuse_pool)
+        if fused and not n4:
+            fused = fscnn.sf_variant_choice(d["f"], n, hw, hw, n4=False, pool=True) > 0
+        if fused:                              # the conv launch stores the pooled tensor only
+            d["y"] = torch.empty(shape(hw // 2), dtype=torch.float32, device="cuda")
         elif d["pool"]:
-            d["p"] = torch.empty(fscnn.n4_shape(n, d["k"], hw // 2, hw // 2), dtype=torch.float32, device="cuda")
-        d["fused"] = bool(d["pool"] and fuse_pool)
+            d["p"] = torch.empty(shape(hw // 2), dtype=torch.float32, device="cuda")
+        d["fused"] = fused
 
 
 def run_step(fscnn, x, dev_layers, n, events=None):
@@ -86,7 +91,7 @@ def run_step(fscnn, x, dev_layers, n, events=None):
             events[li][1].record()
         cur = d["y"]
         if d["pool"] and not d["fused"]:
-            fscnn.maxpool2x2(cur, out=d["p"], layout=fscnn.N4, n=n)
+            fscnn.maxpool2x2(cur, out=d["p"], layout=d["lay_out"], n=n)
             cur = d["p"]
     if shared:
         events[len(dev_layers)].record()
@@ -176,6 +181,127 @@ def probe_gather_fma(torch, iters=20000, work_groups=2048):
     b.record()
     torch.cuda.synchronize()
     return work_groups * 256.0 * iters * 32.0 / (a.elapsed_time(b) * 1e-3) / 1e12
+
+
+def roof_of(flop, nbytes, ms):
+    """Roofline object of one launch (or one step): the roof that takes longer at the published
+    peaks binds; achieved / peak in that roof's unit."""
+    t_hbm, t_alu = nbytes / (HBM_PEAK_GBS * 1e9), flop / (FP32_VECTOR_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_alu:
+        a = nbytes / (ms * 1e-3) / 1e9
+        return dict(bound="hbm", achieved=a, peak=HBM_PEAK_GBS, unit="GB/s", frac=a / HBM_PEAK_GBS)
+    a = flop / (ms * 1e-3) / 1e12
+    return dict(bound="alu", achieved=a, peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s", frac=a / FP32_VECTOR_PEAK_TFLOPS)
+
+
+def layer_bytes(n, c, k, hw, yhw, nnz):
+    """Algorithmic bytes of one sparse-filter launch: x read once, y written once, the compressed
+    filter (value + packed index per non-zero, row pointers) and the bias read once."""
+    return 4.0 * n * (hw * hw * c + yhw * k) + 8.0 * nnz + 4.0 * (k + 1) + 4.0 * k
+
+
+def config_rows(fscnn, torch, inputs, np, oracle, steps=20, check_points=2000):
+    """The small configurations: the two single layers at N=1 and the 13-layer stack at N=1 (90 %
+    weight sparsity), the stack both as 13 launches per step and as one captured HIP graph.  Every
+    row is checked against the oracle before it is timed."""
+    out = {}
+    for name, c in (("config1_single_layer_n1_c16_k32_32x32_keep0.10", inputs.config1()),
+                    ("config2_single_layer_n1_c256_k256_56x56_keep0.05", inputs.config2())):
+        w, x = c["w"], c["x"]
+        f = fscnn.filter_compress(torch.from_numpy(w).cuda())
+        xd = torch.from_numpy(x).cuda()
+        bd = None if c["bias"] is None else torch.from_numpy(c["bias"]).cuda()
+        n, cc, h, wd = x.shape
+        k = w.shape[0]
+        y = fscnn.conv2d_sparse_filter(f, xd, c["stride"], c["pad"], bd, c["relu"])
+        o, a = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, c["stride"], c["pad"], c["bias"],
+                                           c["relu"], want_abs=True)
+        err = rel_err(np, y.cpu().numpy(), o)
+        ms = time_gpu(torch, lambda: fscnn.conv2d_sparse_filter(f, xd, c["stride"], c["pad"], bd, c["relu"], out=y), 200)
+        flop = 2.0 * f.nnz * h * wd * n
+        nbytes = layer_bytes(n, cc, k, h, h * wd, f.nnz)          # square inputs
+        v = fscnn.sf_variant_choice(f, n, h, wd)
+        out[name] = dict(ms_per_launch=ms, effective_gflops=flop / ms / 1e6, algorithmic_gbs=nbytes / ms / 1e6,
+                         max_rel_err=err, kernel=fscnn.sf_variant_name(v) if v > 0 else "direct",
+                         roofline=roof_of(flop, nbytes, ms),
+                         note="back-to-back launches on one stream, HIP events around 200 of them; one "
+                              "image leaves most of the 256 compute units idle")
+        assert err <= 1e-4, (name, err)
+
+    # config 3: the stack at N=1, NCHW tensors throughout, plans and channel-split scratch prepared
+    # beforehand on the stream that runs (and captures) it
+    n = 1
+    x, L, _ = build_stack(fscnn, torch, inputs, n, 0.10, config_id=3)
+    alloc_buffers(fscnn, torch, L, n, True, n4=False)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for d in L:
+            fscnn.filter_prepare(d["f"], n, d["hw"], d["hw"], (1, 1), (1, 1), 0, d["lay_in"], d["lay_out"], d["fused"])
+        run_step(fscnn, x, L, n)
+        side.synchronize()
+        errs = [rel_err(np, g, o) for _, g, o, _, _ in chain_samples(fscnn, torch, np, oracle, x, L, n, check_points)]
+        eager_last = L[-1]["y"].clone()
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+        events = [[ev() for _ in range(len(L) + 1)] for _ in range(steps)]
+        side.synchronize()
+        t0 = time.perf_counter()
+        for st in range(steps):
+            run_step(fscnn, x, L, n, events[st] if all(d["fused"] or not d["pool"] for d in L) else None)
+        side.synchronize()
+        eager_ms = (time.perf_counter() - t0) / steps * 1e3
+        shared = all(d["fused"] or not d["pool"] for d in L)
+        layer_ms = ([float(np.mean([events[st][li].elapsed_time(events[st][li + 1]) for st in range(steps)]))
+                     for li in range(len(L))] if shared else None)
+    # one HIP graph of the same 13 (+ pool) launches: no allocation, no memset node, nothing but
+    # kernel nodes.  Replayed with eager work and synchronisations in between, every replay
+    # compared bit for bit with the eager result, then timed.
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_step(fscnn, x, L, n)
+    replays_equal = True
+    for r in range(4):
+        L[-1]["y"].fill_(-1.0)
+        for d in L[:-1]:
+            d["y"].zero_()                     # eager work of the program's own between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        replays_equal = replays_equal and bool(torch.equal(L[-1]["y"], eager_last))
+    a, b = ev(), ev()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    a.record()
+    for _ in range(steps):
+        graph.replay()
+    b.record()
+    torch.cuda.synchronize()
+    graph_wall_ms = (time.perf_counter() - t0) / steps * 1e3
+    graph_ms = a.elapsed_time(b) / steps
+    feff = [2.0 * d["f"].nnz * d["hw"] ** 2 * n for d in L]
+    byts = [layer_bytes(n, d["c"], d["k"], d["hw"], (d["hw"] // 2) ** 2 if d["fused"] else d["hw"] ** 2, d["f"].nnz)
+            for d in L]
+    F, B = sum(feff), sum(byts)
+    kern = []
+    for d in L:
+        v = fscnn.sf_variant_choice(d["f"], n, d["hw"], d["hw"], n4=False, pool=d["fused"])
+        kern.append(fscnn.sf_variant_name(v) if v > 0 else "direct")
+    row = dict(eager_ms_per_step=eager_ms, graph_ms_per_step=graph_ms, graph_wall_ms_per_step=graph_wall_ms,
+               eager_effective_gflops=F / eager_ms / 1e6, graph_effective_gflops=F / graph_ms / 1e6,
+               graph_algorithmic_gbs=B / graph_ms / 1e6, graph_replays_bit_equal_to_eager=replays_equal,
+               max_rel_err=max(errs), per_layer_rel_err=errs, layer_ms=layer_ms, layer_kernel=kern,
+               pools_merged=[bool(d["fused"]) for d in L if d["pool"]],
+               roofline=roof_of(F, B, graph_ms),
+               note="13 launches per step on one stream (plans and split scratch prepared beforehand) against "
+                    "one replay of a HIP graph that holds the same launches; N=1 leaves the chip mostly idle "
+                    "and the step is bound by launch and dependency latency, not by a roof")
+    if layer_ms is not None:
+        li = int(np.argmax(layer_ms))
+        row["dominant_layer"] = dict(layer=li + 1, kernel=kern[li], ms=layer_ms[li],
+                                     roofline=roof_of(feff[li], byts[li], layer_ms[li]))
+    assert replays_equal and max(errs) <= 1e-4, row
+    out["config3_vgg16_stack_n1_keep0.10"] = row
+    return out
 
 
 def time_gpu(torch, fn, iters):
@@ -529,6 +655,8 @@ def main():
     )
     if not args.no_rows:
         out["other_rows"] = other_rows(fscnn, torch, inputs, np, dev_layers)
+        import oracle
+        out["config_rows"] = config_rows(fscnn, torch, inputs, np, oracle)
     if args.cpu_images > 0:
         out["cpu_baseline"] = cpu_baseline(inputs, args.keep, args.cpu_images)
     print(json.dumps(out))

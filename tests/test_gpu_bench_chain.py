@@ -75,3 +75,44 @@ def test_bench_chain_sampler_is_pinned_by_a_whole_tensor_case(F):
         assert np.array_equal(o, full.ravel()) and np.array_equal(g, got.ravel())
         assert_parity(g, o, a, nmax, "small chain layer %d" % li)
         cur = got
+
+
+def test_bench_chain_config3_full_size_eager_and_as_one_graph(F):
+    """Config 3 as bench.py's config_rows runs it: N=1, 90 % weight sparsity, NCHW tensors throughout,
+    plans and channel-split scratch prepared beforehand on the stream that runs and captures it.
+    The eager chain against the oracle layer by layer; then one HIP graph of the same launches,
+    replayed with eager work and synchronisations in between, every replay bit-equal to the eager
+    result (the channel-split layers add their parts in a fixed order)."""
+    n = 1
+    x, L, _ = bench.build_stack(F, torch, inputs, n, 0.10, config_id=3)
+    bench.alloc_buffers(F, torch, L, n, True, n4=False)
+    assert all(d["lay_in"] == F.NCHW and d["lay_out"] == F.NCHW for d in L)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for d in L:
+            F.filter_prepare(d["f"], n, d["hw"], d["hw"], (1, 1), (1, 1), 0, d["lay_in"], d["lay_out"], d["fused"])
+        out = bench.run_step(F, x, L, n)
+        side.synchronize()
+        assert tuple(out.shape) == (n, 512, 14, 14)
+        seen = 0
+        for li, g, o, a, nmax in bench.chain_samples(F, torch, np, oracle, x, L, n, npts=3000, seed=5):
+            assert_parity(g, o, a, nmax, "config 3 chain layer %d" % (li + 1))
+            seen += 1
+        assert seen == 13
+        eager = [d["y"].clone() for d in L]
+        side.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        bench.run_step(F, x, L, n)
+    for r in range(4):
+        for d in L:
+            d["y"].fill_(float(r) - 7.0)       # eager work between the replays; stale results cannot pass
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for li, (d, e) in enumerate(zip(L, eager)):
+            assert torch.equal(d["y"], e), "replay %d, layer %d" % (r, li + 1)
+    del graph
+    assert torch.cuda.mem_get_info()[0] >= free0 - (64 << 20)     # capture made no large allocation
