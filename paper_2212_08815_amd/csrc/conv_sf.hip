@@ -102,7 +102,9 @@ struct Cfg {
     static constexpr int NT = WAVES * 64;
     static constexpr int NIW = (NI + WAVES - 1) / WAVES;   // lines per wave and image group
     static constexpr int ROWSTEP = PITCH * BV * 4;         // bytes from one tile row to the next
-    static constexpr int FIFO = U == 0 ? 3 : U;            // records held ahead in SGPRs
+    static constexpr int FIFO = U == 0 ? 3 : U;            // records held ahead
+    // records fetched with vector loads instead of scalar ones (see rec_at in the kernel)
+    static constexpr bool VREC = U == 0;
     // loads a wave may leave in flight once the NEXT chunk has to be complete: every wave
     // issues at least IG*(NI/WAVES) lines per chunk, and D-1 younger chunks follow it
     static constexpr int WAITN = (D - 1) * IG * (NI / WAVES) > 63 ? 63 : (D - 1) * IG * (NI / WAVES);
@@ -142,6 +144,24 @@ template <> __device__ inline float vget<4>(const float4 &v, int e)
 __device__ inline void pin(const float2 &v) { asm volatile("" : : "v"(v.x), "v"(v.y)); }
 __device__ inline void pin(const float4 &v) { asm volatile("" : : "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
 
+// The tap reads of the pipelined loop, written as instructions of their own: the compiler does
+// not count them, so the loop can wait for "all but the newest NV reads" (LDS reads return in
+// order) where the compiler, which loses count across a loop's back edge, would wait for all.
+template <int V, int NV, int ROWSTEP> __device__ inline void lds_read_taps(f4v (&dst)[NV], uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst[V]) : "v"(addr), "n"(V * ROWSTEP));
+    if constexpr (V + 1 < NV) lds_read_taps<V + 1, NV, ROWSTEP>(dst, addr);
+}
+// Waits until at most N of this wave's LDS reads (and scalar loads) are in flight, then names
+// the taps so that nothing that uses them is moved in front of the wait.
+template <int N, int NV> __device__ inline void lds_taps_landed(f4v (&buf)[NV])
+{
+    asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(N));
+#pragma unroll
+    for (int v = 0; v < NV; ++v) asm volatile("" : "+v"(buf[v]));
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // Work-groups are dealt round-robin to the 8 XCDs; renumber them so that consecutive logical
 // ids (the channel groups of one input tile) land on the same XCD and share its L2.
 __device__ inline int xcd_remap(int bid, int nblk)
@@ -158,7 +178,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                      const int *__restrict__ segptr, int N, int C, int H, int W, int K, int Ho,
                      int Wo, int ph, int pw, int relu, int NCH, int NG, int tiles_x,
                      int tiles_per_img, int nblk, int csplit, long long part_stride,
-                     int *__restrict__ emit_cnt)
+                     int *__restrict__ emit_cnt, unsigned long long recs_addr)
 {
     using V = typename VecT<G::BV>::T;
     extern __shared__ __align__(256) char ldsb[];
@@ -246,18 +266,65 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
 #pragma unroll
         for (int p = 0; p < G::P; ++p) acc[j][p] = 0.0f;
 
-    // this wave's record stream, its (chunk, slot) boundaries, and the SGPR queue of records
+    // How a record is fetched.  Through the scalar cache (the address is wave-uniform) its fields
+    // land in SGPRs for free, but scalar loads share the LDS reads' counter and return out of
+    // order, so every wait for taps becomes a wait for everything.  VREC: the same address through
+    // a vector load, every lane getting its own copy (the offset of zero is made opaque, or the
+    // compiler would pick the scalar load again): the fields live in vector registers, the taps'
+    // waits can count down one read at a time, and the load costs a slot of the vector memory
+    // pipeline per record -- which only pays where a record feeds many multiply-adds.
+    // It is a buffer load with the records' base in the descriptor, the record's byte position as
+    // the scalar offset and the zero as the vector offset, so the address arithmetic stays on the
+    // scalar unit.  (The host refuses such a configuration for a plan beyond 2^31 bytes.)
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    uint32_t vzero = 0;
+    if constexpr (G::VREC) asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
+    auto rec_at = [&](int idx) -> Rec {
+        if constexpr (G::VREC) {
+            const __amdgpu_buffer_rsrc_t rrs = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<Rec *>(recs), 0, 0x7ffffff0, 0x00020000);
+            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rrs, vzero, idx * (int)sizeof(Rec), 0);
+            // (the halves are taken from the pair viewed as one 64-bit number: taken as vector
+            // elements, this compiler narrows the load to one dword and hands its value to both)
+            const unsigned long long w = __builtin_bit_cast(unsigned long long, v);
+            const uint32_t lo = (uint32_t)w, hi = (uint32_t)(w >> 32);
+            Rec r;
+            r.off = lo;
+            r.val = __builtin_bit_cast(float, hi);
+            return r;
+        } else {
+            return recs[idx];
+        }
+    };
+    // this wave's record stream, its (chunk, slot) boundaries, and the queue of records
     // (ci0 == NCH, an empty part: the entry read here is the next wave's first, or the array's
     // last one; no record is applied)
     const int *seg = segptr + ((long long)(kg * G::WAVES + wave) * NCH + ci0) * G::SLOTS;
     int i = seg[0];
     Rec q[G::FIFO];
 #pragma unroll
-    for (int f = 0; f < G::FIFO; ++f) q[f] = recs[i + f];
+    for (int f = 0; f < G::FIFO; ++f) q[f] = rec_at(i + f);
     int bnd[G::SLOTS];
 #pragma unroll
     for (int j = 0; j < G::SLOTS; ++j) bnd[j] = ci0 < ci1 ? seg[j + 1] : i;
 
+    // Pull the head of this wave's record stream towards the L2: the scalar loads of the hot loop
+    // run only three records ahead, and a stream that was last read a whole pass of the network
+    // ago comes from HBM.  One load, lane l touching the 64-byte line l of the stream (lanes past
+    // its end touch nothing); the data goes to ring slot D, which nobody reads or loads before the
+    // barrier below, and being the oldest load in flight it has landed by any wait further down.
+    // Only where few work-groups share a stream (one per tile and image group): with thousands
+    // of them it is in the L2 anyway, and the extra load only lengthens their short lives
+    // (measured: the 224- and 112-wide layers ran 1.5 times as long with it).
+    if (nblk <= 128 * NG) {
+        const int iend = ci0 < ci1 ? seg[(ci1 - ci0) * G::SLOTS] : i;
+        // (the records' address comes as a plain number of its own: deriving it from `recs` here
+        // would let the compiler assume that the loads below may change the records)
+        const uint64_t base = recs_addr + (uint64_t)i * sizeof(Rec);
+        const int4v rs = {(int)(uint32_t)base, (int)((base >> 32) & 0xffffu), (iend - i) * (int)sizeof(Rec), 0x00020000};
+        static_assert(G::WAVES * 256 <= G::BUF_BYTES, "one 256-byte line per wave fits a ring slot");
+        lds_dma_dword(rs, lds0 + (uint32_t)(G::D * G::BUF_BYTES + wave * 256), lane * 64);
+    }
     // the first D chunks start loading; chunk 0 must have landed before anyone reads it
 #pragma unroll
     for (int d = 0; d < G::D; ++d)
@@ -278,32 +345,28 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
             for (int j = 0; j < G::SLOTS; ++j) nbnd[j] = bnd[G::SLOTS - 1];
         }
         const char *tile = ldsb + (lane_base + (uint32_t)(rbuf * G::BUF_BYTES));
+        const uint32_t tile_lds = lds0 + lane_base + (uint32_t)(rbuf * G::BUF_BYTES);   // the same as an LDS address
         rbuf = rbuf + 1 == G::NB ? 0 : rbuf + 1;
 
         // ---- gather-FMA over this wave's records of the chunk (A5)
         if constexpr (G::U == 0) {
             // Software pipeline (BV = 4).  Invariant at the top of a trip for record i:
             // q[0..2] = records i, i+1, i+2 and the taps of record i are in flight into `cur`.
-            // A trip waits for them (and for the record fetched one trip ago), starts the reads
-            // of record i+1 into the other buffer and the fetch of record i+3, and multiplies
-            // record i meanwhile: the LDS latency hides behind the multiply-adds of the same
-            // wave.  Trips come in pairs (A then B), so every segment starts with its first
-            // record in buffer A; a segment's odd last record is multiplied out of A and only
-            // then are the next record's reads issued into A again.  Reads that run past the
-            // chunk's last record fetch a valid tap of this chunk's tile and are issued again
-            // after the barrier.  The empty statement that names the taps makes the compiler
-            // place its wait there, before the next reads, and the scheduling barriers keep
-            // that order.
+            // A trip starts the reads of record i+1 into the other buffer (its values were
+            // multiplied a trip ago) and the fetch of record i+3, waits until only those newest
+            // NV reads are in flight -- the taps of record i have landed then: a read has two
+            // trips to come back -- and multiplies record i.  Trips come in pairs (A then B), so
+            // every segment starts with its first record in buffer A; a segment's odd last
+            // record is multiplied out of A and only then are the next record's reads issued
+            // into A again.  Reads that run past the chunk's last record fetch a valid tap of
+            // this chunk's tile and are issued again after the barrier.  The tap reads and their
+            // waits are instructions written out here (lds_read_taps, lds_taps_landed): the
+            // records come through vector loads, so that nothing else of this loop counts on
+            // the counter the waits watch.
+            static_assert(G::VREC, "the waits below count LDS reads only");
             f4v tapA[G::NV], tapB[G::NV];
             auto issue = [&](f4v(&dst)[G::NV], uint32_t off) {
-                const char *p = tile + off;
-#pragma unroll
-                for (int v = 0; v < G::NV; ++v) dst[v] = *reinterpret_cast<const f4v *>(p + v * G::ROWSTEP);
-            };
-            auto landed = [&](f4v(&buf)[G::NV]) {
-#pragma unroll
-                for (int v = 0; v < G::NV; ++v) asm volatile("" : : "v"(buf[v]));
-                __builtin_amdgcn_sched_barrier(0);
+                lds_read_taps<0, G::NV, G::ROWSTEP>(dst, tile_lds + off);
             };
             issue(tapA, q[0].off);
 #pragma unroll
@@ -320,17 +383,17 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                     }
                 };
                 auto trip = [&](f4v(&cur)[G::NV], f4v(&nxt)[G::NV]) {
-                    landed(cur);
-                    // A wave whose taps have landed runs its trip -- the reads of the next record
-                    // in one burst, then the multiply-adds -- at raised priority: it is served
-                    // before waves that are about to wait anyway.  (Spreading the reads between
-                    // the multiply-adds measured slower.)  The priority changes end the
-                    // compiler's scheduling region, so the group hints below order nothing in
-                    // the trip itself; they stay because the code the compiler emits for the
-                    // queue rotation after them measured 0.7 % faster with them than without.
-                    __builtin_amdgcn_s_setprio(3);
+                    // The reads of the next record in one burst, then the multiply-adds, at
+                    // raised priority once the taps have landed: such a wave is served before
+                    // waves that are about to wait anyway.  (Spreading the reads between the
+                    // multiply-adds measured slower.)  The priority changes end the compiler's
+                    // scheduling region, so the group hints below order nothing in the trip
+                    // itself; they stay because the code the compiler emits for the queue
+                    // rotation after them measured 0.7 % faster with them than without.
                     issue(nxt, q[1].off);
-                    const Rec fresh = recs[i + 3];
+                    const Rec fresh = rec_at(i + 3);
+                    lds_taps_landed<G::NV, G::NV>(cur);
+                    __builtin_amdgcn_s_setprio(3);
                     mul(cur);
                     __builtin_amdgcn_s_setprio(0);
 #pragma unroll
@@ -349,8 +412,8 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                     trip(tapB, tapA);
                 }
                 if (i < end) {  // odd tail
-                    landed(tapA);
-                    const Rec fresh = recs[i + 3];
+                    lds_taps_landed<0, G::NV>(tapA);
+                    const Rec fresh = rec_at(i + 3);
                     mul(tapA);
                     __builtin_amdgcn_sched_barrier(0);
                     issue(tapA, q[1].off);
@@ -363,7 +426,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
             }
             // the read in flight targets this chunk's buffer: let it land before the barrier
             // below allows that buffer to be overwritten
-            landed(tapA);
+            lds_taps_landed<0, G::NV>(tapA);
         } else
 #pragma unroll
         for (int j = 0; j < G::SLOTS; ++j) {
@@ -388,7 +451,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                 }
                 Rec fresh[G::U];
 #pragma unroll
-                for (int m = 0; m < G::U; ++m) fresh[m] = recs[ni + m];
+                for (int m = 0; m < G::U; ++m) fresh[m] = rec_at(ni + m);
                 __builtin_amdgcn_s_setprio(0);
                 if constexpr (G::U > 1) {
 #pragma unroll
@@ -671,9 +734,12 @@ hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, in
     if (csplit < 1 || (G::POOL && csplit != 1)) return hipErrorInvalidValue;
     const long long nblk = (long long)p.NG * tiles_x * tiles_y * nbat * csplit;
     if (nblk <= 0 || nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    // the vector loads of the records address them with 32-bit byte offsets
+    if (G::VREC && (p.nrec + kPlanSpare) * (long long)sizeof(Rec) >= 0x7ffffff0LL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(conv_sf_tiled_kernel<G>, dim3((unsigned)nblk), dim3(G::NT), G::LDS_BYTES, st,
                        x, y, bias, p.recs, p.segptr, N, C, H, W, K, Ho, Wo, ph, pw, relu, p.NCH,
-                       p.NG, tiles_x, tiles_x * tiles_y, (int)nblk, csplit, part_stride, emit_cnt);
+                       p.NG, tiles_x, tiles_x * tiles_y, (int)nblk, csplit, part_stride, emit_cnt,
+                       (unsigned long long)(uintptr_t)p.recs);
     return hipGetLastError();
 }
 
