@@ -351,7 +351,7 @@ fscnn_status_t fscnn_filter_prepare_ex(fscnn_filter_t *f, int N, int H, int W, i
     s = get_plan(f, v, (hipStream_t)stream, &p);
     if (s != FSCNN_OK || p->direct) return s;
     // the same decision as the convolution call takes
-    const int csplit = (variant == 0 && !pool) ? sf_choose_csplit(v, N, f->K, Ho, Wo, p->NCH) : 1;
+    const int csplit = variant == 0 ? sf_choose_csplit(v, N, f->K, Ho, Wo, p->NCH) : 1;
     if (csplit > 1) {
         float *parts;
         s = split_scratch(f, p, (hipStream_t)stream,
@@ -483,7 +483,7 @@ static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int 
                                         f->S, Ho, Wo, sh, sw, ph, pw, bias_dev, relu, y_dev, st));
     } else {
         // automatic choice only: an explicitly selected configuration runs as it is
-        const int csplit = (variant == 0 && !pool) ? sf_choose_csplit(v, N, f->K, Ho, Wo, p->NCH) : 1;
+        const int csplit = variant == 0 ? sf_choose_csplit(v, N, f->K, Ho, Wo, p->NCH) : 1;
         float *parts = nullptr;
         if (csplit > 1) {
             s = split_scratch(f, p, st, sizeof(float) * (size_t)csplit * (size_t)sf_split_elems(N, f->K, Ho, Wo, out4),

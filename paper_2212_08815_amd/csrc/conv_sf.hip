@@ -712,6 +712,33 @@ __global__ void __launch_bounds__(256) split_sum_kernel(const float *__restrict_
     y[i] = act_apply(v, relu);
 }
 
+// The same with the merged 2x2 / stride-2 max-pool (Alg. 7): the parts hold full-size partial
+// sums, element i of the pooled result is the maximum over its window of the summed parts, then
+// bias and activation (they commute with the maximum, as in the merged epilogue of the kernel).
+__global__ void __launch_bounds__(256) split_sum_pool_kernel(const float *__restrict__ parts, int nparts,
+                                                             long long part_stride, const float *__restrict__ bias,
+                                                             int K, int Ho, int Wo, int inner, int relu,
+                                                             long long n, float *__restrict__ y)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int Hp = Ho / 2, Wp = Wo / 2;
+    const int b = (int)(i % inner);
+    const int px = (int)((i / inner) % Wp);
+    const int py = (int)((i / ((long long)inner * Wp)) % Hp);
+    const long long plane = i / ((long long)inner * Wp * Hp);
+    float m = 0.0f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const long long src = ((plane * Ho + 2 * py + (d >> 1)) * Wo + 2 * px + (d & 1)) * inner + b;
+        float v = parts[src];
+        for (int p = 1; p < nparts; ++p) v += parts[(long long)p * part_stride + src];
+        m = d == 0 || v > m ? v : m;
+    }
+    if (bias) m += bias[(int)(plane % K)];
+    y[i] = act_apply(m, relu);
+}
+
 // ---------------------------------------------------------------- variant table
 using LaunchFn = hipError_t (*)(const SfPlan &, const float *, int, int, int, int, int, int, int,
                                 int, int, const float *, int, float *, int, long long, int *, hipStream_t);
@@ -1001,18 +1028,26 @@ hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, i
     const Variant *t = variants(&n);
     if (p.variant < 1 || p.variant > n) return hipErrorInvalidValue;
     const Variant &v = t[p.variant - 1];
-    LaunchFn fn = (pool ? v.pool : v.fn)[in4 ? 1 : 0][out4 ? 1 : 0];
+    // (the channel-split mode launches the form without the pool: its finishing pass pools)
+    LaunchFn fn = (pool && csplit == 1 ? v.pool : v.fn)[in4 ? 1 : 0][out4 ? 1 : 0];
     if (!fn) return hipErrorInvalidValue;
     if (csplit > 1) {
-        // every part stores its partial sums into its own copy of the output (parts: csplit *
-        // sf_split_elems floats of scratch), then one pass adds the copies, bias and activation
+        // every part stores its partial sums into its own copy of the full-size output (parts:
+        // csplit * sf_split_elems floats of scratch), then one pass adds the copies, pools where
+        // asked to, and applies bias and activation
         if (!parts) return hipErrorInvalidValue;
         const long long total = sf_split_elems(N, K, Ho, Wo, out4);
         if (emit_cnt) return hipErrorInvalidValue;   // the parts' sums are not final results
         hipError_t e = fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, parts, csplit, total, nullptr, st);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, parts,
-                           csplit, total, bias, K, (long long)Ho * Wo, out4 ? 4 : 1, relu, total, y);
+        if (pool) {
+            const long long pooled = sf_split_elems(N, K, Ho / 2, Wo / 2, out4);
+            hipLaunchKernelGGL(split_sum_pool_kernel, dim3((unsigned)((pooled + 255) / 256)), dim3(256), 0, st,
+                               parts, csplit, total, bias, K, Ho, Wo, out4 ? 4 : 1, relu, pooled, y);
+        } else {
+            hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, parts,
+                               csplit, total, bias, K, (long long)Ho * Wo, out4 ? 4 : 1, relu, total, y);
+        }
         return hipGetLastError();
     }
     if (emit_cnt && (out4 || pool)) return hipErrorInvalidValue;

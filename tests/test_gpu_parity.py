@@ -741,6 +741,28 @@ def test_channel_split_mode_is_bit_reproducible_and_matches_the_oracle(F):
         assert_parity(got[0], o, a, row_nmax(w), "channel split %r" % ((n, c, k, hw, lay),))
 
 
+def test_channel_split_mode_with_the_merged_pool(F):
+    """The same mode where the 2x2 max-pool is merged into the call: the parts hold full-size partial
+    sums and the finishing pass pools.  Against the oracle's convolution followed by its plain
+    max-pool (odd sizes: the last row and column drop out), twice for the same bits."""
+    for (n, c, k, h, w_, lay) in [(1, 512, 512, 28, 28, "nchw"), (1, 256, 96, 15, 17, "nchw"), (3, 300, 70, 14, 14, "n4"),
+                                  (8, 512, 512, 14, 14, "n4")]:
+        x, w, b = inputs.random_layer(700 + c + h, n, c, k, h, w_, 3, 3, 0.1)
+        f = F.filter_compress(dev(w))
+        xl = F.N4 if lay == "n4" else F.NCHW
+        xd = dev(to_n4(x)) if lay == "n4" else dev(x)
+        F.filter_prepare(f, n, h, w_, (1, 1), (1, 1), x_layout=xl, y_layout=xl, pool=True)
+        runs = [F.conv2d_sparse_filter(f, xd, (1, 1), (1, 1), dev(b), True, x_layout=xl, y_layout=xl, n=n, pool=True)
+                for _ in range(3)]
+        torch.cuda.synchronize()
+        got = [from_n4(host(y), n) if lay == "n4" else host(y) for y in runs]
+        assert got[0].shape == (n, k, h // 2, w_ // 2)
+        assert all(np.array_equal(bits(g), bits(got[0])) for g in got[1:])
+        o, a = oracle.conv2d_sparse_filter(x, oracle.filter_compress(w), w.shape, (1, 1), (1, 1), b, True, want_abs=True)
+        assert_parity(got[0], oracle.maxpool2x2(o), oracle.maxpool2x2(a.astype(np.float32)).astype(np.float64) * (1 + 1e-6),
+                      row_nmax(w), "channel split with pool %r" % ((n, c, k, h, w_, lay),))
+
+
 def test_filter_handle_serves_two_streams_at_once(F):
     """One compressed filter, two streams launching convolutions on different inputs at the same
     time (the plan is built once, under the handle's lock): both results equal the ones computed
