@@ -1,7 +1,11 @@
 """Builds libfscnn.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree, and beside it
 libfscnn_bench_probe.so, the measurement helper that only bench.py loads.
 
-    python -m paper_2212_08815_amd.build [--force]
+    python -m paper_2212_08815_amd.build [--force] [--sanitize-host]
+
+--sanitize-host builds a second copy, libfscnn_hostsan.so, whose HOST code (argument checks,
+handles, plans: everything that is not a kernel) is instrumented with AddressSanitizer and
+UndefinedBehaviorSanitizer; tests/README_sanitize.txt says how the tests run against it.
 
 hipcc cross-compiles without a GPU.  Objects go to _build/ (not committed), the
 shared library next to this file so that it travels with the source tree.
@@ -38,6 +42,31 @@ def _compile(src, obj, extra):
     cmd = [HIPCC] + FLAGS + extra + ["-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     return src, r.returncode, r.stdout + r.stderr
+
+
+SAN_LIB = os.path.join(HERE, "libfscnn_hostsan.so")
+# each -fsanitize= directly behind -Xarch_host: device code is never instrumented
+SAN_FLAGS = ["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+
+
+def build_host_sanitized(verbose=True):
+    """libfscnn_hostsan.so: the library with its host code under ASan + UBSan."""
+    objdir = os.path.join(OBJDIR, "hostsan")
+    os.makedirs(objdir, exist_ok=True)
+    objs = []
+    for s in SOURCES:
+        obj = os.path.join(objdir, s.replace(".hip", ".o"))
+        objs.append(obj)
+        src, rc, out = _compile(os.path.join(CSRC, s), obj, SAN_FLAGS)
+        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+        if verbose and out.strip():
+            print(out)
+        if rc != 0:
+            raise RuntimeError("hipcc failed on %s" % src)
+    subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-fsanitize=address",
+                           "-fsanitize=undefined", "-shared-libsan", "-o", SAN_LIB] + objs)
+    return SAN_LIB
 
 
 def build(force=False, extra_flags=(), verbose=True):
@@ -77,3 +106,5 @@ def build(force=False, extra_flags=(), verbose=True):
 
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv))
+    if "--sanitize-host" in sys.argv:
+        print(build_host_sanitized())

@@ -12,7 +12,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfscnn.so")
+# FSCNN_LIB names another build of the same library (the host-sanitized one of build.py --sanitize-host)
+LIB_PATH = os.environ.get("FSCNN_LIB") or os.path.join(_HERE, "libfscnn.so")
 _lib = None
 
 OK = 0
