@@ -314,8 +314,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     // its end touch nothing); the data goes to ring slot D, which nobody reads or loads before the
     // barrier below, and being the oldest load in flight it has landed by any wait further down.
     // Only where few work-groups share a stream (one per tile and image group): with thousands
-    // of them it is in the L2 anyway, and the extra load only lengthens their short lives
-    // (measured: the 224- and 112-wide layers ran 1.5 times as long with it).
+    // of them it is in the L2 anyway.
     if (nblk <= 128 * NG) {
         const int iend = ci0 < ci1 ? seg[(ci1 - ci0) * G::SLOTS] : i;
         // (the records' address comes as a plain number of its own: deriving it from `recs` here
