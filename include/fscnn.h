@@ -114,10 +114,15 @@ fscnn_status_t fscnn_filter_prepare_ex(fscnn_filter_t *f, int N, int H, int W, i
  *   [3] number of chunks  [4] number of groups  [5] tile rows per channel
  *   [6] pitch (vectors per tile row)  [7] BV floats per vector (images interleaved)
  *   [8] records (= nonzeros)  [9] 1 if the direct (untiled) kernel serves this geometry
- *   [10] SLOTS channels per wave  [11] WAVES per group (KG = SLOTS*WAVES); rest 0.
+ *   [10] SLOTS channels per wave  [11] WAVES per group (KG = SLOTS*WAVES)
+ *   [12] 1 for the taps-outer form (banks without zeros, few input channels); rest 0.
  * Bucket b = ((group*WAVES + wave)*chunks + chunk)*SLOTS + slot holds the entries of output
  * channel group*KG + wave*SLOTS + slot whose input channel lies in the chunk; a record's
- * byte offset is (((c mod CC)*rows + r)*pitch + s)*BV*4.
+ * byte offset is (((c mod CC)*rows + r)*pitch + s)*BV*4.  Where [12] is set the records are
+ * laid out differently -- per (group, wave, chunk), CC*R*S groups of SLOTS records, one group
+ * per tap (c mod CC, r, s) in ascending order, record j of a group = {the tap's byte offset,
+ * the weight of channel group*KG + wave*SLOTS + j there, 0.0f where none is stored} -- [8] is
+ * their number, and segptr still describes the stored entries as above.
  * If segptr_host / rec_off_host / rec_val_host are non-NULL they receive
  * segptr[groups*chunks*KG + 1], and per record the LDS byte offset and the weight.
  * Pass NULL pointers first to learn the sizes. */

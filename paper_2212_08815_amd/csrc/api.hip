@@ -125,7 +125,8 @@ fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan *
     p->NCH = (f->C + g.CC - 1) / g.CC;
     p->NG = (f->K + g.KG - 1) / g.KG;
     const long long nb = (long long)p->NG * p->NCH * g.KG;
-    const long long cap = f->nnz;
+    // records: one per stored value; the taps-outer form lists every tap of every chunk instead
+    const long long cap = g.DENSE ? (long long)p->NG * g.WAVES * p->NCH * g.CC * f->R * f->S * g.SLOTS : f->nnz;
     if (!fits_int(nb + 1) || cap + kPlanSpare >= (1LL << 31)) {
         delete p;
         return FSCNN_ERR_UNSUPPORTED;
@@ -146,8 +147,10 @@ fscnn_status_t get_plan(fscnn_filter_t *f, int variant, hipStream_t st, SfPlan *
         e = launch_plan_count(f->rowptr, f->idx, f->K, f->R * f->S, g, p->NCH, p->NG, cnt, st);
     if (e == hipSuccess) e = launch_exclusive_scan(cnt, p->segptr, nb, cnt + nb, st);
     if (e == hipSuccess)
-        e = launch_plan_fill(f->rowptr, f->idx, f->val, f->K, f->R, f->S, g, p->NCH, p->NG,
-                             p->segptr, p->recs, st);
+        e = g.DENSE ? launch_plan_fill_dense(f->rowptr, f->idx, f->val, f->K, f->C, f->R, f->S, g, p->NCH,
+                                             p->NG, cap, p->recs, st)
+                    : launch_plan_fill(f->rowptr, f->idx, f->val, f->K, f->R, f->S, g, p->NCH, p->NG,
+                                       p->segptr, p->recs, st);
     // The plan may be used from other streams and `cnt` is released here: wait for the build.
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (cnt) (void)hipFree(cnt);
@@ -179,8 +182,9 @@ fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int
     }
     // N4 tensors need four images per lane whatever the batch size; the choice goes by the
     // output's extent (about the input's divided by the stride)
+    const bool no_zeros = f->nnz == (long long)f->K * f->C * f->R * f->S;
     int v = tiled_ok ? sf_choose_variant(n4 && N < 4 ? 4 : N, f->C, f->K, (H + sh - 1) / sh, (W + sw - 1) / sw,
-                                         f->R, f->S, sh, pool, n4)
+                                         f->R, f->S, sh, pool, n4, no_zeros)
                      : 0;
     *resolved = v > 0 ? v : -1;
     return FSCNN_OK;
@@ -398,6 +402,7 @@ fscnn_status_t fscnn_filter_plan_export(fscnn_filter_t *f, int N, int H, int W, 
     params_host[8] = (int)p->nrec;
     params_host[10] = p->g.SLOTS;
     params_host[11] = p->g.WAVES;
+    params_host[12] = p->g.DENSE;
     const long long nb = (long long)p->NG * p->NCH * p->g.KG;
     if (segptr_host)
         FSCNN_HIP(hipMemcpy(segptr_host, p->segptr, sizeof(int) * (size_t)(nb + 1), hipMemcpyDeviceToHost));

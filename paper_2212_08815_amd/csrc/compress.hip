@@ -267,6 +267,42 @@ __global__ void plan_fill_kernel(const int *__restrict__ rowptr, const uint32_t 
     }
 }
 
+// The plan of the taps-outer form: for every (group, wave, chunk), CC*R*S groups of SLOTS records
+// {LDS byte offset of tap (c mod CC, r, s), weight of output channel (group*WAVES + wave)*SLOTS + j
+// at that tap}, a zero weight where the row stores nothing there (or k, c lie past the bank).
+__global__ void plan_fill_dense_kernel(const int *__restrict__ rowptr, const uint32_t *__restrict__ idx,
+                                       const float *__restrict__ val, int K, int C, int R, int S, int CC,
+                                       int SLOTS, int WAVES, int NCH, int NG, int IN_ROWS, int PITCH,
+                                       int BV, long long nrec, Rec *__restrict__ recs)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < kPlanSpare) {
+        Rec z;
+        z.off = 0u;
+        z.val = 0.0f;
+        recs[nrec + i] = z;
+    }
+    if (i >= nrec) return;
+    const int RS = R * S, T = CC * RS;
+    const int j = (int)(i % SLOTS);
+    const int t = (int)((i / SLOTS) % T);
+    const int ci = (int)((i / ((long long)SLOTS * T)) % NCH);
+    const long long gw = i / ((long long)SLOTS * T * NCH);   // group * WAVES + wave
+    const int k = (int)(gw * SLOTS + j);
+    const int cl = t / RS, rs = t % RS;
+    const int c = ci * CC + cl;
+    Rec rec;
+    rec.off = (uint32_t)((((cl * IN_ROWS) + rs / S) * PITCH + rs % S) * BV * 4);
+    rec.val = 0.0f;
+    if (k < K && c < C) {
+        const uint32_t flat = (uint32_t)(c * RS + rs);
+        const int lo = rowptr[k], hi = rowptr[k + 1];
+        const int at = lower_bound_u32(idx, lo, hi, flat);
+        if (at < hi && idx[at] == flat) rec.val = val[at];
+    }
+    recs[i] = rec;
+}
+
 // ---- A7: compressed activation, rows = pixels, columns = channels ----------------------
 // One thread per (pixel, step of CC channels): threads of a work-group take consecutive pixels
 // of one step, so the reads of a channel plane are contiguous.  The exclusive scan of the counts
@@ -454,6 +490,16 @@ hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float 
     hipLaunchKernelGGL(plan_fill_kernel, dim3(blocks_for(nb, kBlock)), dim3(kBlock), 0, st, rowptr,
                        idx, val, K, R, S, g.CC, g.SLOTS, g.WAVES, NCH, NG, g.IN_ROWS, g.PITCH, g.BV, g.STRIDE,
                        segptr, recs);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan_fill_dense(const int *rowptr, const uint32_t *idx, const float *val, int K, int C,
+                                  int R, int S, const SfGeom &g, int NCH, int NG, long long nrec, Rec *recs,
+                                  hipStream_t st)
+{
+    const long long n = nrec > kPlanSpare ? nrec : kPlanSpare;
+    hipLaunchKernelGGL(plan_fill_dense_kernel, dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, st, rowptr, idx,
+                       val, K, C, R, S, g.CC, g.SLOTS, g.WAVES, NCH, NG, g.IN_ROWS, g.PITCH, g.BV, nrec, recs);
     return hipGetLastError();
 }
 

@@ -31,6 +31,7 @@ struct SfGeom {
     int IN_ROWS, PITCH;                     // LDS rows per channel, BV-vectors per row
     int KG;                                 // output channels per work-group
     int STRIDE;                             // stride (both axes) the instance is built for
+    int DENSE;                              // 1: the plan lists every tap of every chunk, SLOTS weights per tap
     int lds_bytes;
 };
 
@@ -147,6 +148,10 @@ hipError_t launch_plan_count(const int *rowptr, const uint32_t *idx, int K, int 
 hipError_t launch_plan_fill(const int *rowptr, const uint32_t *idx, const float *val, int K, int R,
                             int S, const SfGeom &g, int NCH, int NG, const int *segptr, Rec *recs,
                             hipStream_t st);
+// the taps-outer plan (SfGeom::DENSE): nrec = NG*WAVES*NCH*CC*R*S*SLOTS records plus the spare ones
+hipError_t launch_plan_fill_dense(const int *rowptr, const uint32_t *idx, const float *val, int K, int C,
+                                  int R, int S, const SfGeom &g, int NCH, int NG, long long nrec, Rec *recs,
+                                  hipStream_t st);
 hipError_t launch_input_count(const float *x, int N, int C, int H, int W, int CC, int NCH, int *cnt,
                               hipStream_t st);
 // also zeroes the `spare` entries that follow the last stored one (cptr's last element says where)
@@ -162,7 +167,8 @@ int sf_variant_count();
 const char *sf_variant_name(int variant);
 // false if the variant cannot serve RxS filters at this stride
 bool sf_variant_geom(int variant, int R, int S, int sh, int sw, SfGeom *g);
-int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool, bool n4);
+int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool, bool n4,
+                      bool no_zeros = false);
 bool sf_variant_has_layout(int variant, int in4, int out4, int pool);
 // csplit > 1: `parts` is scratch of csplit * sf_split_elems(...) floats (one copy of y per part)
 long long sf_split_elems(int N, int K, int Ho, int Wo, int out4);

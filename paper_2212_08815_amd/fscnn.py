@@ -192,7 +192,7 @@ def filter_plan_export(f, N, H, W, stride=(1, 1), pad=(0, 0), variant=0):
     out = dict(variant=int(params[0]), CC=int(params[1]), KG=int(params[2]), NCH=int(params[3]),
                NG=int(params[4]), IN_ROWS=int(params[5]), PITCH=int(params[6]), BV=int(params[7]),
                nrec=int(params[8]), direct=bool(params[9]), SLOTS=int(params[10]),
-               WAVES=int(params[11]))
+               WAVES=int(params[11]), DENSE=int(params[12]))
     if out["direct"]:
         return out
     nb = out["NG"] * out["NCH"] * out["KG"]

@@ -115,6 +115,21 @@ def test_plan_regroup_decodes_to_the_canonical_rows(F):
         assert not p["direct"] and p["variant"] == v
         CC, KG, NCH, NG, SL, WV = p["CC"], p["KG"], p["NCH"], p["NG"], p["SLOTS"], p["WAVES"]
         assert NCH == -(-C // CC) and NG == -(-K // KG) and KG == SL * WV
+        if p["DENSE"]:
+            # the taps-outer form: every tap of every chunk, SLOTS weights per tap, zeros where
+            # the bank stores nothing
+            T = CC * R * S
+            assert p["nrec"] == NG * WV * NCH * T * SL
+            off = p["rec_off"].reshape(NG, WV, NCH, T, SL)
+            val = p["rec_val"].reshape(NG, WV, NCH, T, SL)
+            tt = np.arange(T)
+            want_off = ((((tt // (R * S)) * p["IN_ROWS"]) + (tt % (R * S)) // S) * p["PITCH"] + tt % S) * p["BV"] * 4
+            assert np.array_equal(off, np.broadcast_to(want_off[None, None, None, :, None], off.shape))
+            dense = np.zeros((NG * KG, NCH * CC, R, S), np.float32)
+            dense[:K, :C] = w
+            want = dense.reshape(NG, WV, SL, NCH, T).transpose(0, 1, 3, 4, 2)
+            assert np.array_equal(bits(val), bits(want))
+            continue
         seg = p["segptr"]
         assert seg[0] == 0 and np.all(np.diff(seg) >= 0) and seg[-1] == orp[-1] == p["nrec"]
         q = p["rec_off"].astype(np.int64) // (4 * p["BV"])
@@ -718,6 +733,41 @@ def test_config5_sparse_input_point(F):
     for v in range(0, F.si_variant_count() + 1):
         yp = host(F.conv2d_sparse_input_prepared(xs, d, c["stride"], c["pad"], dev(c["bias"]), c["relu"], variant=v))
         assert_parity(yp.ravel()[flat], o, a, 512 * 9, "config5 prepared sparse input variant %d" % v)
+
+
+def test_first_layer_form_for_banks_without_zeros(F):
+    """A bank without zeros over three input channels (an RGB first layer) is served, where the launch
+    fills the chip, by the form that walks taps in the outer loop and feeds every tap it reads to all
+    channels of the wave.  Same sums in the same order as the record-stream forms: bit-equal to them,
+    and within the rule against the oracle; layouts, merged pool, ragged sizes."""
+    n, c, k, h, w_ = 16, 3, 64, 118, 130
+    x, w, b = inputs.random_layer(901, n, c, k, h, w_, 3, 3, keep=1.0)
+    assert np.count_nonzero(w) == w.size
+    f = F.filter_compress(dev(w))
+    names = {v: F.sf_variant_name(v) for v in range(1, F.sf_variant_count() + 1)}
+    for n4 in (False, True):
+        for pool in (False, True):
+            v = F.sf_variant_choice(f, n, h, w_, n4=n4, pool=pool)
+            assert "_u5_" in names[v], (n4, pool, names[v])
+    o, a = oracle.conv2d_dense(x, w, (1, 1), (1, 1), b, True, want_abs=True)
+    xd, bd = dev(x), dev(b)
+    y = host(F.conv2d_sparse_filter(f, xd, (1, 1), (1, 1), bd, True))
+    assert_parity(y, o, a, c * 9, "first-layer form, NCHW")
+    other = [v for v, nm in names.items() if "_u1_" in nm and "_cc3_" in nm and not nm.endswith(("_st2", "_r1s1"))][0]
+    y1 = host(F.conv2d_sparse_filter(f, xd, (1, 1), (1, 1), bd, True, variant=other))
+    assert np.array_equal(bits(y), bits(y1))
+    y4 = F.conv2d_sparse_filter(f, xd, (1, 1), (1, 1), bd, True, x_layout=F.NCHW, y_layout=F.N4, n=n)
+    assert np.array_equal(bits(from_n4(host(y4), n)), bits(y))
+    yp = F.conv2d_sparse_filter(f, dev(to_n4(x)), (1, 1), (1, 1), bd, True, x_layout=F.N4, y_layout=F.N4, n=n, pool=True)
+    assert np.array_equal(bits(from_n4(host(yp), n)), bits(oracle.maxpool2x2(y)))
+    # a single zero in the bank: the automatic choice goes back to the record-stream forms
+    w0 = w.copy()
+    w0[5, 1, 2, 0] = 0.0
+    f0 = F.filter_compress(dev(w0))
+    assert "_u5_" not in names[F.sf_variant_choice(f0, n, h, w_)]
+    # ... and so does a bank whose channel count leaves idle channels in a work-group
+    f1 = F.filter_compress(dev(w[:40]))
+    assert "_u5_" not in names[F.sf_variant_choice(f1, n, h, w_)]
 
 
 def test_channel_split_mode_is_bit_reproducible_and_matches_the_oracle(F):
