@@ -934,6 +934,7 @@ const Variant *variants(int *count)
         FSCNN_V411(32, 2, 2, 2, 16, 20, 4, 2), // 31  1x1, wider than 128: 32x4 tiles, 2 channels per wave
         FSCNN_V4P(16, 4, 4, 2, 16, 15, 0, 2),  // 32  up to 16x16 images with many output channels: one 16x16 tile per image, pipelined
         FSCNN_V4P(16, 4, 2, 8, 8, 3, 5, 2),    // 33  banks without zeros over up to 3 input channels (an RGB first layer): taps outer, 8 channels per wave, 16x8 tiles (32x4: 4 % slower, 64x2: 20 %)
+        FSCNN_V4P(16, 4, 2, 8, 4, 3, 5, 2),    // 34  the same with 32 channels per work-group (4 waves), for banks of 32, 96, ... channels
     };
     *count = (int)(sizeof(table) / sizeof(table[0]));
     return table;
@@ -1002,9 +1003,10 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int strid
     // a bank without zeros over at most 3 input channels (the first layer of a network fed RGB
     // images): the taps-outer form, where it fills the chip and its 64 channels per work-group
     // are all real ones (measured on 3->64 at 224x224, N = 32: 0.148 -> 0.123 ms)
-    if (no_zeros && stride == 1 && R == 3 && S == 3 && C <= 3 && N >= 4 && K % 64 == 0 &&
-        sf_blocks(t[33 - 1].g, N, K, H, W) >= 512)
-        return 33;
+    if (no_zeros && stride == 1 && R == 3 && S == 3 && C <= 3 && N >= 4 && K % 32 == 0) {
+        const int v = K % 64 == 0 ? 33 : 34;
+        if (sf_blocks(t[v - 1].g, N, K, H, W) >= 512) return v;
+    }
     if (stride == 2) {   // 3x3 only, four-image forms, no pooled form; H, W are the output's here
         if (R != 3 || S != 3 || pool) return 0;
         const int first = W > 64 ? 28 : W > 16 ? 27 : 24;   // measured on Darknet-53's down-sampling layers, N = 32

@@ -768,6 +768,13 @@ def test_first_layer_form_for_banks_without_zeros(F):
     # ... and so does a bank whose channel count leaves idle channels in a work-group
     f1 = F.filter_compress(dev(w[:40]))
     assert "_u5_" not in names[F.sf_variant_choice(f1, n, h, w_)]
+    # 32 channels: the four-wave form of the same loop
+    f2 = F.filter_compress(dev(w[:32]))
+    v2 = F.sf_variant_choice(f2, 32, h, w_)
+    assert "_u5_" in names[v2] and "_w4_" in names[v2]
+    x2 = np.concatenate([x, x[::-1]], 0)
+    y2 = host(F.conv2d_sparse_filter(f2, dev(x2), (1, 1), (1, 1), dev(b[:32]), True))
+    assert np.array_equal(bits(y2[:n]), bits(y[:, :32])) and np.array_equal(bits(y2[n:]), bits(y[::-1, :32]))
 
 
 def test_channel_split_mode_is_bit_reproducible_and_matches_the_oracle(F):
