@@ -31,7 +31,10 @@ extern "C" {
 typedef struct fscnn_filter fscnn_filter_t; /* compressed filter bank (device buffers inside)   */
 typedef struct fscnn_input fscnn_input_t;   /* compressed activation tensor (device buffers)    */
 
-typedef enum {
+/* Status codes and layout codes travel as plain int, so that a caller's out-of-range value is an
+ * ordinary integer the library can refuse rather than an invalid enumerator. */
+typedef int fscnn_status_t;
+enum {
     FSCNN_OK = 0,
     FSCNN_ERR_NULL = 1,        /* a required pointer is NULL                                   */
     FSCNN_ERR_SHAPE = 2,       /* non-positive size, negative pad, empty output, size overflow */
@@ -40,7 +43,7 @@ typedef enum {
     FSCNN_ERR_ALLOC = 5,       /* device or host allocation failed                             */
     FSCNN_ERR_DEVICE = 6,      /* HIP runtime error (no device, launch failure, ...)           */
     FSCNN_ERR_HANDLE = 7       /* not a live handle (bad magic word / already destroyed)       */
-} fscnn_status_t;
+};
 
 const char *fscnn_status_string(fscnn_status_t s);
 
@@ -53,7 +56,8 @@ const char *fscnn_status_string(fscnn_status_t s);
  *                      convolution kernel keeps in LDS (one 16-byte read feeds four images), so
  *                      chained layers that pass N4 tensors stage their input with contiguous
  *                      16-byte loads and store their output with 16-byte stores. */
-typedef enum { FSCNN_LAYOUT_NCHW = 0, FSCNN_LAYOUT_N4 = 1 } fscnn_layout_t;
+typedef int fscnn_layout_t;
+enum { FSCNN_LAYOUT_NCHW = 0, FSCNN_LAYOUT_N4 = 1 };
 
 /* Output extent of a convolution (host only).  Alg. 1 step 3 and Alg. 6 step 3 give
  * (H_I - H_F)/S + 1; with the symmetric zero padding of Sec. 5 ("Other layers") this is

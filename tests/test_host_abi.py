@@ -40,6 +40,7 @@ def test_out_shape_and_status_strings(L):
     assert L.fscnn_conv2d_out_shape(5, 5, 3, 3, 1, 1, 0, 0, None, None) == 1
     for s in range(8):
         assert len(L.fscnn_status_string(s)) > 0
+    assert L.fscnn_status_string(99) == L.fscnn_status_string(-1) != L.fscnn_status_string(7)   # any int is answered
     n = fscnn.sf_variant_count()
     assert n >= 1 and all(fscnn.sf_variant_name(v) for v in range(1, n + 1))
     assert fscnn.sf_variant_name(0) == "" and fscnn.sf_variant_name(n + 1) == ""
@@ -96,6 +97,54 @@ def test_argument_checks_come_before_device_work(L):
     assert L.fscnn_sf_variant_choice(None, 1, 4, 4, 1, 1, 0, 0, ctypes.byref(v)) == 1
     assert L.fscnn_sf_variant_choice(ctypes.byref(junk), 1, 4, 4, 1, 1, 0, 0, None) == 1
     assert L.fscnn_sf_variant_choice(ctypes.byref(junk), 1, 4, 4, 1, 1, 0, 0, ctypes.byref(v)) == 7
+
+
+def test_argument_checks_of_the_remaining_entry_points(L):
+    fake = ctypes.c_void_p(256)
+    odd = ctypes.c_void_p(260)          # not 16-byte aligned: the N4 layout needs float4 accesses
+    junk = (ctypes.c_ubyte * 512)()
+    jp = ctypes.byref(junk)
+    ll = ctypes.c_longlong
+    conv = (1, 1, 4, 4, 1, 1, 0, 0, None, 0)                    # N, C, H, W, stride, pad, bias, relu
+    for fn in (L.fscnn_conv2d_sparse_filter_ex, L.fscnn_conv2d_sparse_filter_pool2x2):
+        assert fn(None, fake, *conv, fake, 0, 0, 0, None) == 1
+        assert fn(jp, fake, *conv, fake, 0, 0, 0, None) == 7
+    assert L.fscnn_conv2d_sparse_filter_v(None, fake, *conv, fake, 0, None) == 1
+    assert L.fscnn_conv2d_sparse_filter_v(jp, fake, *conv, fake, 0, None) == 7
+    assert L.fscnn_conv2d_sparse_filter_emit_into(None, fake, *conv, None, None, jp) == 1
+    assert L.fscnn_conv2d_sparse_filter_emit_into(jp, fake, *conv, None, None, None) == 1
+    assert L.fscnn_conv2d_sparse_filter_emit_into(jp, fake, *conv, None, None, jp) == 7
+    assert L.fscnn_filter_export(None, fake, fake, fake) == 1 and L.fscnn_filter_export(jp, fake, fake, fake) == 7
+    assert L.fscnn_input_export(None, fake, fake, fake) == 1 and L.fscnn_input_export(jp, fake, fake, fake) == 7
+    assert L.fscnn_filter_prepare(None, 1, 4, 4, 1, 1, 0, 0, 0, None) == 1
+    assert L.fscnn_filter_prepare(jp, 1, 4, 4, 1, 1, 0, 0, 0, None) == 7
+    assert L.fscnn_filter_prepare_ex(None, 1, 4, 4, 1, 1, 0, 0, 0, 0, 0, 0, None) == 1
+    assert L.fscnn_filter_prepare_ex(jp, 1, 4, 4, 1, 1, 0, 0, 0, 0, 0, 0, None) == 7
+    params = (ctypes.c_int * 16)()
+    assert L.fscnn_filter_plan_export(None, 1, 4, 4, 1, 1, 0, 0, 0, params, None, None, None) == 1
+    assert L.fscnn_filter_plan_export(jp, 1, 4, 4, 1, 1, 0, 0, 0, None, None, None, None) == 1
+    assert L.fscnn_filter_plan_export(jp, 1, 4, 4, 1, 1, 0, 0, 0, params, None, None, None) == 7
+    # layout conversion: NCHW <-> N4 only, out of place, N4 side aligned to 16 bytes
+    other = ctypes.c_void_p(512)
+    assert L.fscnn_layout_convert(None, 1, 1, 2, 2, 0, other, 1, None) == 1
+    assert L.fscnn_layout_convert(fake, 0, 1, 2, 2, 0, other, 1, None) == 2
+    assert L.fscnn_layout_convert(fake, 1, 1, 2, 2, 0, other, 0, None) == 4      # same layout on both sides
+    assert L.fscnn_layout_convert(fake, 1, 1, 2, 2, 0, other, 7, None) == 4      # unknown layout code
+    assert L.fscnn_layout_convert(fake, 1, 1, 2, 2, 0, fake, 1, None) == 4       # in place
+    assert L.fscnn_layout_convert(fake, 1, 1, 2, 2, 0, odd, 1, None) == 4
+    assert L.fscnn_layout_convert(fake, 1 << 15, 1 << 15, 2, 2, 0, other, 1, None) == 4   # 2^31 elements or more
+    assert L.fscnn_maxpool2x2_ex(None, 1, 1, 2, 2, fake, 0, None) == 1
+    assert L.fscnn_maxpool2x2_ex(fake, 1, 1, 2, 1, other, 0, None) == 2
+    assert L.fscnn_maxpool2x2_ex(fake, 1, 1, 2, 2, other, 5, None) == 4
+    assert L.fscnn_maxpool2x2_ex(fake, 1, 1, 2, 2, odd, 1, None) == 4
+    # the transpose that allocates nothing refuses what its fixed scratch cannot hold
+    na = L.fscnn_sparse_transpose_noalloc
+    assert na(fake, fake, fake, 0, 2, ll(1), fake, fake, fake, None) == 2
+    assert na(None, fake, fake, 2, 2, ll(1), fake, fake, fake, None) == 1
+    assert na(fake, fake, fake, 2, 2, ll(-1), fake, fake, fake, None) == 2
+    assert na(fake, fake, fake, 2, 2, ll(1 << 31), fake, fake, fake, None) == 2
+    assert na(fake, fake, fake, 2, 2, ll((1 << 31) - 1), fake, fake, fake, None) == 4
+    assert L.fscnn_sf_variant_count() >= 1
 
 
 def test_no_cpu_fallback_without_a_device(L):
