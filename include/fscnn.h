@@ -151,6 +151,16 @@ fscnn_status_t fscnn_sf_variant_choice(const fscnn_filter_t *f, int N, int H, in
                                        int stride_h, int stride_w, int n4, int pool,
                                        int *variant_out);
 
+/* How a launch of configuration `variant` (1..count) lays one or two images over the four image
+ * slots of a lane: with NCHW tensors on both sides (`n4` zero) and N <= 2, a four-image
+ * configuration gives the slots to *bands_out = 4 / N horizontal bands of *band_rows_out output
+ * rows of each image (even where `pool` is nonzero), so that no slot computes on an image that is
+ * not there; a band's halo rows are its neighbours' rows, and every output is still the sum over
+ * its filter's stored entries in the order of the plan.  Otherwise *bands_out = 1 and
+ * *band_rows_out = Ho.  Host-only. */
+fscnn_status_t fscnn_sf_band_choice(int variant, int N, int Ho, int n4, int pool, int *bands_out,
+                                    int *band_rows_out);
+
 /* Sparse-filter convolution (Alg. 6: every output element, all filters; inner product of
  * Alg. 2 over the stored nonzeros only; no kernel flip; padding as index shift):
  *   y[n,k,oy,ox] = sum over stored (c,r,s,v) of filter k of

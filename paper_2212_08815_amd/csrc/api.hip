@@ -183,8 +183,16 @@ fscnn_status_t resolve_variant(const fscnn_filter_t *f, int N, int H, int W, int
     // N4 tensors need four images per lane whatever the batch size; the choice goes by the
     // output's extent (about the input's divided by the stride)
     const bool no_zeros = f->nnz == (long long)f->K * f->C * f->R * f->S;
-    int v = tiled_ok ? sf_choose_variant(n4 && N < 4 ? 4 : N, f->C, f->K, (H + sh - 1) / sh, (W + sw - 1) / sw,
-                                         f->R, f->S, sh, pool, n4, no_zeros)
+    // one or two images through NCHW tensors: the four-image forms, their image slots filled with
+    // bands of the image (sf_choose_bands), so the choice sees four slots of a quarter (half) the height
+    int slots = n4 && N < 4 ? 4 : N, rows = (H + sh - 1) / sh;
+    const bool banded = !n4 && N <= 2;
+    if (banded) {
+        rows = (rows + 4 / N - 1) / (4 / N);
+        slots = 4;
+    }
+    int v = tiled_ok ? sf_choose_variant(slots, f->C, f->K, rows, (W + sw - 1) / sw, f->R, f->S, sh, pool, n4,
+                                         no_zeros, banded)
                      : 0;
     *resolved = v > 0 ? v : -1;
     return FSCNN_OK;
@@ -354,8 +362,10 @@ fscnn_status_t fscnn_filter_prepare_ex(fscnn_filter_t *f, int N, int H, int W, i
     SfPlan *p;
     s = get_plan(f, v, (hipStream_t)stream, &p);
     if (s != FSCNN_OK || p->direct) return s;
-    // the same decision as the convolution call takes
-    const int csplit = variant == 0 ? sf_choose_csplit(v, N, f->K, Ho, Wo, p->NCH) : 1;
+    // the same decisions as the convolution call takes
+    int band_shift, band_h;
+    sf_choose_bands(v, N, Ho, in4 || out4, pool != 0, &band_shift, &band_h);
+    const int csplit = variant == 0 ? sf_choose_csplit(v, N << band_shift, f->K, band_h, Wo, p->NCH) : 1;
     if (csplit > 1) {
         float *parts;
         s = split_scratch(f, p, (hipStream_t)stream,
@@ -448,6 +458,18 @@ fscnn_status_t fscnn_sf_variant_choice(const fscnn_filter_t *f, int N, int H, in
     return resolve_variant(f, N, H, W, sh, sw, 0, variant_out, n4 != 0, pool != 0);
 }
 
+fscnn_status_t fscnn_sf_band_choice(int variant, int N, int Ho, int n4, int pool, int *bands_out,
+                                    int *band_rows_out)
+{
+    if (!bands_out || !band_rows_out) return FSCNN_ERR_NULL;
+    if (N <= 0 || Ho <= 0) return FSCNN_ERR_SHAPE;
+    if (variant < 1 || variant > sf_variant_count()) return FSCNN_ERR_UNSUPPORTED;
+    int shift;
+    sf_choose_bands(variant, N, Ho, n4 != 0, pool != 0, &shift, band_rows_out);
+    *bands_out = 1 << shift;
+    return FSCNN_OK;
+}
+
 // emit_cnt / counted: sparse output emission.  When the launch that serves the call can count the
 // non-zero results per (pixel, step of 8 channels) in its epilogue it writes them to emit_cnt and
 // sets *counted; otherwise the caller counts in a pass of its own.
@@ -488,16 +510,18 @@ static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int 
                                         f->S, Ho, Wo, sh, sw, ph, pw, bias_dev, relu, y_dev, st));
     } else {
         // automatic choice only: an explicitly selected configuration runs as it is
-        const int csplit = variant == 0 ? sf_choose_csplit(v, N, f->K, Ho, Wo, p->NCH) : 1;
+        int band_shift, band_h;
+        sf_choose_bands(v, N, Ho, in4 || out4, pool != 0, &band_shift, &band_h);
+        const int csplit = variant == 0 ? sf_choose_csplit(v, N << band_shift, f->K, band_h, Wo, p->NCH) : 1;
         float *parts = nullptr;
         if (csplit > 1) {
             s = split_scratch(f, p, st, sizeof(float) * (size_t)csplit * (size_t)sf_split_elems(N, f->K, Ho, Wo, out4),
                               &parts);
             if (s != FSCNN_OK) return s;
         }
-        int *cnt = (emit_cnt && csplit == 1 && !out4 && !pool) ? emit_cnt : nullptr;
+        int *cnt = (emit_cnt && csplit == 1 && !out4 && !pool && band_shift == 0) ? emit_cnt : nullptr;
         FSCNN_HIP(launch_conv_sf_tiled(*p, x_dev, N, C, H, W, f->K, Ho, Wo, ph, pw, bias_dev, relu,
-                                       y_dev, in4, out4, pool, csplit, parts, cnt, st));
+                                       y_dev, in4, out4, pool, csplit, parts, cnt, band_shift, band_h, st));
         if (counted) *counted = cnt != nullptr;
     }
     return FSCNN_OK;

@@ -184,7 +184,8 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                      const int *__restrict__ segptr, int N, int C, int H, int W, int K, int Ho,
                      int Wo, int ph, int pw, int relu, int NCH, int NG, int tiles_x,
                      int tiles_per_img, int nblk, int csplit, long long part_stride,
-                     int *__restrict__ emit_cnt, unsigned long long recs_addr)
+                     int *__restrict__ emit_cnt, unsigned long long recs_addr, int band_shift,
+                     int band_h)
 {
     using V = typename VecT<G::BV>::T;
     extern __shared__ __align__(256) char ldsb[];
@@ -205,6 +206,13 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     const int n0 = (lid / (NG * tiles_per_img)) * G::IMGS;
     const int ty0 = (t / tiles_x) * G::TH;
     const int tx0 = (t % tiles_x) * G::TW;
+    // Band mode (NCHW tensors on both sides, one or two images): the image slots of a lane group
+    // would stay empty, so they are given horizontal bands of one image instead: slot v of the
+    // launch (n0 counts slots) is band v mod 2^band_shift of image v >> band_shift, a band being
+    // band_h output rows; ty0 and the tile's rows then count from the band's first row, a band's
+    // halo rows are its neighbours' rows, and rows past band_h belong to the next band and are not
+    // stored.  band_shift = 0: slots are images and band_h = Ho.
+    const int bsh_in = G::IN4 ? 0 : band_shift, bsh_out = G::OUT4 ? 0 : band_shift;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -228,11 +236,12 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
         const int cp = e / (G::IN_ROWS * G::PITCH);   // (channel, plane) of the chunk
         const int rem = e % (G::IN_ROWS * G::PITCH);
         const int cl = cp / G::PL, plane = cp % G::PL;
-        const int gy = ty0 * G::STRIDE - ph + (rem / G::PITCH) * G::STRIDE + plane / G::STRIDE;
+        const int band = b & ((1 << bsh_in) - 1), img = b >> bsh_in;   // of this lane's image slot
+        const int gy = (ty0 + band * band_h) * G::STRIDE - ph + (rem / G::PITCH) * G::STRIDE + plane / G::STRIDE;
         const int gx = tx0 * G::STRIDE - pw + (rem % G::PITCH) * G::STRIDE + plane % G::STRIDE;
         const bool ok = e < G::IG_ELEMS && gy >= 0 && gy < H && gx >= 0 && gx < W;
         const int pix = cl * HW + gy * W + gx;
-        goff[q] = !ok ? kInvalidOff : G::IN4 ? pix * 16 : (b * C * HW + pix) * 4;
+        goff[q] = !ok ? kInvalidOff : G::IN4 ? pix * 16 : (img * C * HW + pix) * 4;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ldsb;
     // Lines q with q % nparts == part only: the loads of a chunk are issued in SLOTS portions
@@ -242,9 +251,9 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
         const int crem = C - ci * G::CC;  // channels left from this chunk on (> 0)
 #pragma unroll
         for (int g = 0; g < G::IG; ++g) {
-            const int n = n0 + g * G::BV;
+            const int n = (n0 + g * G::BV) >> bsh_in;   // first image of the group
             int nvalid = N - n;
-            nvalid = nvalid > G::BV ? G::BV : nvalid;
+            nvalid = nvalid > (G::BV >> bsh_in) ? (G::BV >> bsh_in) : nvalid;
             // NCHW: the group's first image from channel ci*CC on, up to the end of its last
             // valid image; N4: the group's block from channel ci*CC on
             const long long first = G::IN4 ? ((long long)(n / 4) * C + (long long)ci * G::CC) * HW * 4
@@ -536,6 +545,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
         // is completed across lanes l and l^32 and stored by the first group.
         constexpr bool ODD = G::NV % 2 != 0;
         const int Hp = Ho / 2, Wp = Wo / 2;
+        const int bhp = band_h >> 1;   // pooled rows of a band (band_h is even in band mode, else Ho)
         const long long pplane = (long long)Hp * Wp;
         const int px = ox >> 1;
 #pragma unroll
@@ -554,7 +564,7 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                     m = act_apply(m, relu);
                     r[b] = m;
                 }
-                const bool ok = writer && (lx & 1) == 0 && py < Hp && px < Wp;
+                const bool ok = writer && (lx & 1) == 0 && py < bhp && px < Wp;   // py: row of the band
                 if constexpr (G::OUT4) {
                     const int n = n0 + ig * 4;
                     if (ok && n < N)
@@ -564,8 +574,10 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                 } else {
 #pragma unroll
                     for (int b = 0; b < G::BV; ++b) {
-                        const int n = n0 + ig * G::BV + b;
-                        if (ok && n < N) y[((long long)n * K + k) * pplane + (long long)py * Wp + px] = r[b];
+                        const int slot = n0 + ig * G::BV + b;
+                        const int n = slot >> bsh_out, gpy = (slot & ((1 << bsh_out) - 1)) * bhp + py;
+                        if (ok && n < N && gpy < Hp)
+                            y[((long long)n * K + k) * pplane + (long long)gpy * Wp + px] = r[b];
                     }
                 }
             };
@@ -626,12 +638,14 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
         } else {
 #pragma unroll
             for (int b = 0; b < G::BV; ++b) {
-                const int n = n0 + ig * G::BV + b;
+                const int slot = n0 + ig * G::BV + b;
+                const int n = slot >> bsh_out, row0 = (slot & ((1 << bsh_out) - 1)) * band_h;
                 float *yk = y + ((long long)n * K + k) * plane;
 #pragma unroll
                 for (int v = 0; v < G::NV; ++v) {
-                    const int oy = ty0 + lh * G::NV + v;
-                    if (n < N && oy < Ho && ox < Wo) {
+                    const int ly = ty0 + lh * G::NV + v;   // row of the band (of the image without bands)
+                    const int oy = row0 + ly;
+                    if (n < N && ly < band_h && oy < Ho && ox < Wo) {
                         if (csplit > 1) {
                             yk[(long long)oy * Wo + ox] = acc[j][v * G::BV + b];
                             continue;
@@ -780,12 +794,13 @@ __global__ void __launch_bounds__(256) split_sum_pool_kernel(const float *__rest
 
 // ---------------------------------------------------------------- variant table
 using LaunchFn = hipError_t (*)(const SfPlan &, const float *, int, int, int, int, int, int, int,
-                                int, int, const float *, int, float *, int, long long, int *, hipStream_t);
+                                int, int, const float *, int, float *, int, long long, int *, int, int,
+                                hipStream_t);
 
 template <class G>
 hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K, int Ho,
                         int Wo, int ph, int pw, const float *bias, int relu, float *y, int csplit,
-                        long long part_stride, int *emit_cnt, hipStream_t st)
+                        long long part_stride, int *emit_cnt, int band_shift, int band_h, hipStream_t st)
 {
     static_assert(G::LDS_BYTES <= 160 * 1024, "tile exceeds the 160 KB LDS of a gfx950 CU");
     if (G::LDS_BYTES > 64 * 1024) {
@@ -794,9 +809,17 @@ hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, in
             hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
         if (attr != hipSuccess) return attr;
     }
+    // band mode: the image slots of the launch are bands of band_h output rows (see the kernel)
+    if (band_shift != 0) {
+        if (G::IN4 || G::OUT4 || G::BV != 4 || band_shift < 0 || band_shift > 2 || band_h < 1 ||
+            (G::POOL && band_h % 2 != 0) || emit_cnt || ((long long)N << band_shift) > 0x7fffffffLL)
+            return hipErrorInvalidValue;
+    } else {
+        band_h = Ho;
+    }
     const int tiles_x = (Wo + G::TW - 1) / G::TW;
-    const int tiles_y = (Ho + G::TH - 1) / G::TH;
-    const int nbat = (N + G::IMGS - 1) / G::IMGS;
+    const int tiles_y = (band_h + G::TH - 1) / G::TH;
+    const int nbat = ((N << band_shift) + G::IMGS - 1) / G::IMGS;
     if (csplit < 1 || (G::POOL && csplit != 1)) return hipErrorInvalidValue;
     const long long nblk = (long long)p.NG * tiles_x * tiles_y * nbat * csplit;
     if (nblk <= 0 || nblk > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -805,7 +828,7 @@ hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, in
     hipLaunchKernelGGL(conv_sf_tiled_kernel<G>, dim3((unsigned)nblk), dim3(G::NT), G::LDS_BYTES, st,
                        x, y, bias, p.recs, p.segptr, N, C, H, W, K, Ho, Wo, ph, pw, relu, p.NCH,
                        p.NG, tiles_x, tiles_x * tiles_y, (int)nblk, csplit, part_stride, emit_cnt,
-                       (unsigned long long)(uintptr_t)p.recs);
+                       (unsigned long long)(uintptr_t)p.recs, band_shift, band_h);
     return hipGetLastError();
 }
 
@@ -996,7 +1019,7 @@ static long long sf_blocks(const SfGeom &g, int N, int K, int Ho, int Wo)
 // would launch too few work-groups to cover the 256 compute units, or that has no pooled form
 // when one is asked for, yields to the next one.
 int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool, bool n4,
-                      bool no_zeros)
+                      bool no_zeros, bool banded)
 {
     int n;
     const Variant *t = variants(&n);
@@ -1023,6 +1046,11 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int strid
         return 20;
     }
     if (R != 3 || S != 3) return 0;
+    // One or two images in band mode (N counts the slots, H a band's rows): the work is small and
+    // what counts is the number of work-groups and how short each one's chain of chunks is, so the
+    // form with two channels per wave and the largest chunks, which the channel split then cuts
+    // into parts (measured on the VGG16-shaped stack at N = 1, every layer from 224x224 to 14x14)
+    if (banded && !(W > 64 && C <= 8)) return 3;
     int pref[4];
     // Fewer than four images: the one-image-per-lane forms only pay on the widest layers; from
     // 112x112 down they launch too few work-groups, and the four-image forms with idle image
@@ -1064,6 +1092,22 @@ int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int strid
     return best;
 }
 
+// Band mode (see the kernel): with NCHW tensors on both sides and one or two images, a four-image
+// configuration fills its image slots with 4 / N horizontal bands of each image.  band_h: output
+// rows per band, even where the merged pool pairs rows.  shift = 0: no bands, band_h = Ho.
+void sf_choose_bands(int variant, int N, int Ho, bool n4, bool pool, int *shift, int *band_h)
+{
+    int n;
+    const Variant *t = variants(&n);
+    *shift = 0;
+    *band_h = Ho;
+    if (variant < 1 || variant > n || t[variant - 1].g.BV != 4 || n4 || N > 2) return;
+    *shift = N == 1 ? 2 : 1;
+    int h = (Ho + (1 << *shift) - 1) >> *shift;
+    if (pool) h += h & 1;
+    *band_h = h;
+}
+
 long long sf_split_elems(int N, int K, int Ho, int Wo, int out4)
 {
     return (out4 ? ((long long)N + 3) / 4 * 4 : (long long)N) * K * Ho * Wo;
@@ -1072,7 +1116,7 @@ long long sf_split_elems(int N, int K, int Ho, int Wo, int out4)
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
                                 float *y, int in4, int out4, int pool, int csplit, float *parts,
-                                int *emit_cnt, hipStream_t st)
+                                int *emit_cnt, int band_shift, int band_h, hipStream_t st)
 {
     int n;
     const Variant *t = variants(&n);
@@ -1088,7 +1132,8 @@ hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, i
         if (!parts) return hipErrorInvalidValue;
         const long long total = sf_split_elems(N, K, Ho, Wo, out4);
         if (emit_cnt) return hipErrorInvalidValue;   // the parts' sums are not final results
-        hipError_t e = fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, parts, csplit, total, nullptr, st);
+        hipError_t e = fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, parts, csplit, total, nullptr,
+                          band_shift, band_h, st);
         if (e != hipSuccess) return e;
         if (pool) {
             const long long pooled = sf_split_elems(N, K, Ho / 2, Wo / 2, out4);
@@ -1101,7 +1146,7 @@ hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, i
         return hipGetLastError();
     }
     if (emit_cnt && (out4 || pool)) return hipErrorInvalidValue;
-    return fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, 1, 0, emit_cnt, st);
+    return fn(p, x, N, C, H, W, K, Ho, Wo, ph, pw, bias, relu, y, 1, 0, emit_cnt, band_shift, band_h, st);
 }
 
 // How many ways the input channels are split for a launch: small problems (deep layers at small

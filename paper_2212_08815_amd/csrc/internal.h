@@ -168,7 +168,7 @@ const char *sf_variant_name(int variant);
 // false if the variant cannot serve RxS filters at this stride
 bool sf_variant_geom(int variant, int R, int S, int sh, int sw, SfGeom *g);
 int sf_choose_variant(int N, int C, int K, int H, int W, int R, int S, int stride, bool pool, bool n4,
-                      bool no_zeros = false);
+                      bool no_zeros = false, bool banded = false);
 bool sf_variant_has_layout(int variant, int in4, int out4, int pool);
 // csplit > 1: `parts` is scratch of csplit * sf_split_elems(...) floats (one copy of y per part)
 long long sf_split_elems(int N, int K, int Ho, int Wo, int out4);
@@ -178,7 +178,11 @@ long long sf_split_elems(int N, int K, int Ho, int Wo, int out4);
 hipError_t launch_conv_sf_tiled(const SfPlan &p, const float *x, int N, int C, int H, int W, int K,
                                 int Ho, int Wo, int ph, int pw, const float *bias, int relu,
                                 float *y, int in4, int out4, int pool, int csplit, float *parts,
-                                int *emit_cnt, hipStream_t st);
+                                int *emit_cnt, int band_shift, int band_h, hipStream_t st);
+// band_shift, band_h of a launch: 4 / N bands of band_h output rows per image where a four-image
+// configuration serves one or two images through NCHW tensors (then the work-groups of the launch,
+// and with them the channel split, go by N << band_shift slots of band_h rows); else 0 and Ho
+void sf_choose_bands(int variant, int N, int Ho, bool n4, bool pool, int *band_shift, int *band_h);
 // 1, or the number of parts the input-channel range is split into for a small problem
 int sf_choose_csplit(int variant, int N, int K, int Ho, int Wo, int NCH);
 hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const float *val,

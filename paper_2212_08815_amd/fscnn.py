@@ -34,7 +34,7 @@ EXPORTS = [
     "fscnn_sparse_transpose", "fscnn_sparse_tensor_transpose", "fscnn_sparse_transpose_workspace",
     "fscnn_dense_filter_prepare", "fscnn_dense_filter_destroy", "fscnn_conv2d_sparse_input_prepared",
     "fscnn_si_variant_count", "fscnn_conv2d_sparse_filter_leaky", "fscnn_sparse_transpose_noalloc",
-    "fscnn_filter_prepare_ex",
+    "fscnn_filter_prepare_ex", "fscnn_sf_band_choice",
 ]
 
 NCHW, N4 = 0, 1      # fscnn_layout_t
@@ -119,6 +119,14 @@ def sf_variant_choice(f, N, H, W, stride=(1, 1), n4=False, pool=False):
                                          _i(1 if n4 else 0), _i(1 if pool else 0), ctypes.byref(v)),
            "fscnn_sf_variant_choice")
     return int(v.value)
+
+
+def sf_band_choice(variant, N, Ho, n4=False, pool=False):
+    """fscnn_sf_band_choice -> (bands per image, output rows per band) of a launch."""
+    b, r = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().fscnn_sf_band_choice(_i(variant), _i(N), _i(Ho), _i(1 if n4 else 0), _i(1 if pool else 0),
+                                      ctypes.byref(b), ctypes.byref(r)), "fscnn_sf_band_choice")
+    return int(b.value), int(r.value)
 
 
 class SparseFilter:

@@ -186,6 +186,44 @@ def test_conv_sparse_filter_matches_oracle_all_variants(F, case):
         assert_parity(g, o, a, row_nmax(w), "case %r variant %d" % (case, v))
 
 
+@pytest.mark.parametrize("n,h,w_,pad", [(1, 30, 21, (1, 1)), (1, 13, 40, (1, 1)), (2, 9, 18, (1, 1)), (1, 5, 7, (0, 0)),
+                                        (1, 3, 3, (1, 1)), (2, 2, 35, (1, 1)), (1, 61, 17, (2, 2)), (2, 28, 28, (1, 1))])
+def test_band_mode_for_one_or_two_images(F, n, h, w_, pad):
+    # One or two images through NCHW tensors: the four-image configurations give a lane's image
+    # slots to bands of the image.  Heights that do not divide into the bands, bands shorter than
+    # a tile and shorter than the halo, heights below the number of bands; with and without the
+    # merged pool (odd heights: the pool drops the last row), whole tensors against the oracle;
+    # integer data: bit-exact.
+    c, k = 21, 34
+    x, w, b = inputs.random_layer(n * 1000 + h * 10 + w_, n, c, k, h, w_, 3, 3, 0.3, integer=True)
+    want = oracle.conv2d_dense(x, w, (1, 1), pad, b, True)
+    ho, wo = want.shape[2:]
+    f = F.filter_compress(dev(w))
+    banded = 0
+    for v in [0] + tiled_variants(F):
+        vv = v or F.sf_variant_choice(f, n, h, w_)
+        for pool in (False, True):
+            if pool and (ho < 2 or wo < 2):
+                continue
+            bands, rows = F.sf_band_choice(vv, n, ho, pool=pool) if vv > 0 else (1, ho)
+            if vv > 0 and F.sf_variant_name(vv).startswith("bv4"):
+                assert bands == 4 // n and bands * rows >= ho and (not pool or rows % 2 == 0)
+                assert (rows - (2 if pool else 1)) * bands < ho, "the shortest bands that cover the image"
+                banded += 1
+            else:
+                assert (bands, rows) == (1, ho)
+            try:
+                got = host(F.conv2d_sparse_filter(f, dev(x), (1, 1), pad, dev(b), True, variant=v, pool=pool))
+            except F.FscnnError as e:
+                assert e.status == 4 and v != 0 and pool
+                continue
+            ref = oracle.maxpool2x2(want) if pool else want
+            assert np.array_equal(got, ref), "n %d %dx%d variant %d pool %d bands %d x %d rows" % (n, h, w_, v, pool, bands, rows)
+    assert banded >= 8
+    assert F.sf_band_choice(F.sf_variant_choice(f, n, h, w_, n4=True), n, ho, n4=True) == (1, ho)   # N4 tensors: no bands
+    assert F.sf_band_choice(F.sf_variant_choice(f, 3, h, w_), 3, ho) == (1, ho)                     # three images: none
+
+
 def test_integer_data_is_bit_exact_all_variants(F):
     # every partial sum is an exact small integer: any summation order gives the same bits
     x, w, b = inputs.random_layer(31, 2, 21, 34, 19, 67, 3, 3, keep=0.3, integer=True)

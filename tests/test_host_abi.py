@@ -145,6 +145,25 @@ def test_argument_checks_of_the_remaining_entry_points(L):
     assert na(fake, fake, fake, 2, 2, ll(1 << 31), fake, fake, fake, None) == 2
     assert na(fake, fake, fake, 2, 2, ll((1 << 31) - 1), fake, fake, fake, None) == 4
     assert L.fscnn_sf_variant_count() >= 1
+    bands, rows = ctypes.c_int(), ctypes.c_int()
+    assert L.fscnn_sf_band_choice(1, 1, 8, 0, 0, None, ctypes.byref(rows)) == 1
+    assert L.fscnn_sf_band_choice(1, 0, 8, 0, 0, ctypes.byref(bands), ctypes.byref(rows)) == 2
+    assert L.fscnn_sf_band_choice(0, 1, 8, 0, 0, ctypes.byref(bands), ctypes.byref(rows)) == 4
+
+
+def test_band_choice_is_host_arithmetic():
+    from paper_2212_08815_amd import fscnn
+    four = [v for v in range(1, fscnn.sf_variant_count() + 1) if fscnn.sf_variant_name(v).startswith("bv4")]
+    other = [v for v in range(1, fscnn.sf_variant_count() + 1) if not fscnn.sf_variant_name(v).startswith("bv4")]
+    assert four and other
+    for v in four:
+        assert fscnn.sf_band_choice(v, 1, 56) == (4, 14) and fscnn.sf_band_choice(v, 2, 56) == (2, 28)
+        assert fscnn.sf_band_choice(v, 1, 14) == (4, 4) and fscnn.sf_band_choice(v, 1, 28, pool=True) == (4, 8)
+        assert fscnn.sf_band_choice(v, 1, 1) == (4, 1) and fscnn.sf_band_choice(v, 2, 7, pool=True) == (2, 4)
+        assert fscnn.sf_band_choice(v, 3, 56) == (1, 56) and fscnn.sf_band_choice(v, 32, 56) == (1, 56)
+        assert fscnn.sf_band_choice(v, 1, 56, n4=True) == (1, 56)
+    for v in other:
+        assert fscnn.sf_band_choice(v, 1, 56) == (1, 56)
 
 
 def test_no_cpu_fallback_without_a_device(L):
