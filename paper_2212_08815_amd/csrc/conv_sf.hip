@@ -227,21 +227,56 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
     // ---- staging table (A4): for each LDS line this wave fills, the global byte offset of the
     // float that lands in this lane's dword, relative to channel ci*CC of the group's first
     // image.  The same table serves every chunk and image group.
+    // An element of the region is (channel-plane cp, row, col), numbered in that order; a wave's
+    // consecutive lines lie STEP elements apart, so only its first line is taken apart by
+    // division and the others follow by adding STEP's digits with carries (with 18 lines per wave
+    // for NCHW input, the divisions and 32-bit multiplications of a direct computation kept the
+    // vector ALUs busy for several microseconds before the first load was issued, which is most
+    // of a work-group's life on a small problem).
     const int HW = H * W;
     int goff[G::NIW];
-#pragma unroll
-    for (int q = 0; q < G::NIW; ++q) {
-        const int d = (wave + q * G::WAVES) * 64 + lane;  // dword (NCHW) or vector (N4) of the region
-        const int e = G::IN4 ? d : d / G::BV, b = G::IN4 ? 0 : d % G::BV;
-        const int cp = e / (G::IN_ROWS * G::PITCH);   // (channel, plane) of the chunk
-        const int rem = e % (G::IN_ROWS * G::PITCH);
-        const int cl = cp / G::PL, plane = cp % G::PL;
+    {
+        constexpr int STEP = G::WAVES * 64 / (G::IN4 ? 1 : G::BV);
+        constexpr int RP = G::IN_ROWS * G::PITCH;
+        constexpr int S_CP = STEP / RP, S_ROW = (STEP % RP) / G::PITCH, S_COL = (STEP % RP) % G::PITCH;
+        static_assert(G::IN4 || (G::WAVES * 64) % G::BV == 0, "a lane keeps its image slot from line to line");
+        const int d0 = wave * 64 + lane;   // dword (NCHW) or vector (N4) of the region, first line
+        const int e0 = G::IN4 ? d0 : d0 / G::BV, b = G::IN4 ? 0 : d0 % G::BV;
+        int cp = e0 / RP, row = (e0 % RP) / G::PITCH, col = (e0 % RP) % G::PITCH;
         const int band = b & ((1 << bsh_in) - 1), img = b >> bsh_in;   // of this lane's image slot
-        const int gy = (ty0 + band * band_h) * G::STRIDE - ph + (rem / G::PITCH) * G::STRIDE + plane / G::STRIDE;
-        const int gx = tx0 * G::STRIDE - pw + (rem % G::PITCH) * G::STRIDE + plane % G::STRIDE;
-        const bool ok = e < G::IG_ELEMS && gy >= 0 && gy < H && gx >= 0 && gx < W;
-        const int pix = cl * HW + gy * W + gx;
-        goff[q] = !ok ? kInvalidOff : G::IN4 ? pix * 16 : (img * C * HW + pix) * 4;
+        const int gy0 = (ty0 + band * band_h) * G::STRIDE - ph, gx0 = tx0 * G::STRIDE - pw;
+        const uint32_t img_off = G::IN4 ? 0u : (uint32_t)img * (uint32_t)C * (uint32_t)HW;
+        // (offsets in unsigned arithmetic: an entry that is not `ok` may wrap, and is not used)
+        const uint32_t uW = (uint32_t)W, uHW = (uint32_t)HW;
+        uint32_t off = 0;
+        if constexpr (G::PL == 1) off = (uint32_t)cp * uHW + (uint32_t)(gy0 + row) * uW + (uint32_t)(gx0 + col);
+#pragma unroll
+        for (int q = 0; q < G::NIW; ++q) {
+            int gy, gx;
+            if constexpr (G::PL == 1) {
+                gy = gy0 + row;
+                gx = gx0 + col;
+            } else {
+                const int cl = cp / G::PL, plane = cp % G::PL;
+                gy = gy0 + row * G::STRIDE + plane / G::STRIDE;
+                gx = gx0 + col * G::STRIDE + plane % G::STRIDE;
+                off = (uint32_t)cl * uHW + (uint32_t)gy * uW + (uint32_t)gx;
+            }
+            const bool ok = cp < G::CC * G::PL && gy >= 0 && gy < H && gx >= 0 && gx < W;
+            goff[q] = !ok ? kInvalidOff : G::IN4 ? (int)(off * 16u) : (int)((img_off + off) * 4u);
+            // the next line of this wave
+            const bool c1 = col + S_COL >= G::PITCH;
+            const int dcol = S_COL - (c1 ? G::PITCH : 0);
+            const int drow0 = S_ROW + (c1 ? 1 : 0);
+            const bool c2 = row + drow0 >= G::IN_ROWS;
+            col += dcol;
+            row += drow0 - (c2 ? G::IN_ROWS : 0);
+            cp += S_CP + (c2 ? 1 : 0);
+            if constexpr (G::PL == 1)
+                off += (c2 ? (uint32_t)(S_CP + 1) * uHW : (uint32_t)S_CP * uHW) +
+                       (c1 ? (uint32_t)(S_ROW + 1) * uW : (uint32_t)S_ROW * uW) -
+                       (c2 ? (uint32_t)G::IN_ROWS * uW : 0u) + (uint32_t)dcol;
+        }
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ldsb;
     // Lines q with q % nparts == part only: the loads of a chunk are issued in SLOTS portions
