@@ -167,11 +167,16 @@ fscnn_status_t fscnn_sf_band_choice(int variant, int N, int Ho, int n4, int pool
  *                  v * x[n,c,oy*stride_h - pad_h + r, ox*stride_w - pad_w + s]   (0 outside)
  *                  (+ bias_dev[k] if bias_dev != NULL) (then max(.,0) if relu != 0).
  * x_dev: N x C x H x W, y_dev: N x K x Ho x Wo (must not alias x), bias_dev: K or NULL.
- * fp32 accumulation in an order fixed by the plan (results are run-to-run identical), except
- * for small problems (at most 128 work-groups with the automatic configuration): there the
- * input-channel range is split over several work-groups whose partial sums are combined with
- * atomic adds in arrival order, so the last bits may differ between runs; an explicitly selected
- * configuration (fscnn_conv2d_sparse_filter_v / _ex with variant > 0) never splits.
+ * fp32 accumulation in an order fixed by the plan: results are run-to-run identical.  For small
+ * problems (at most 128 work-groups with the automatic configuration) the input-channel range is
+ * split over several work-groups; each stores its partial sums into a copy of its own (scratch
+ * that belongs to the handle's plan, one buffer per stream) and a finishing pass adds the copies
+ * in the order of the parts, so this mode is reproducible too, but its sums are grouped
+ * differently from those of an explicitly selected configuration (fscnn_conv2d_sparse_filter_v /
+ * _ex with variant > 0), which never splits.
+ * The batch may be of any size that N, and the number of work-groups, hold as an int: images are
+ * addressed with 64-bit offsets.  One image is bounded: C*H*W and K*Ho*Wo must be below 2^31,
+ * and beyond C*H*W*16 < 2^31 bytes the untiled direct kernel serves the call.
  * Asynchronous on `stream`.  FSCNN_ERR_MISMATCH if C differs from the handle's. */
 fscnn_status_t fscnn_conv2d_sparse_filter(fscnn_filter_t *f, const float *x_dev, int N, int C,
                                           int H, int W, int stride_h, int stride_w, int pad_h,

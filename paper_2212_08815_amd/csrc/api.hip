@@ -231,8 +231,9 @@ fscnn_status_t check_conv_args(const fscnn_filter_t *f, const float *x, int N, i
     fscnn_status_t s = out_shape(H, W, f->R, f->S, sh, sw, ph, pw, Ho, Wo);
     if (s != FSCNN_OK) return s;
     if (C != f->C) return FSCNN_ERR_MISMATCH;
-    if (!fits_int((long long)N * C * H * W) || !fits_int((long long)N * f->K * *Ho * *Wo))
-        return FSCNN_ERR_UNSUPPORTED;
+    // one image's tensors are indexed with ints; images are addressed with 64-bit offsets, so the
+    // batch is bounded only by the number of work-groups a launch can have (checked there)
+    if (!fits_int((long long)C * H * W) || !fits_int((long long)f->K * *Ho * *Wo)) return FSCNN_ERR_UNSUPPORTED;
     if (x == y) return FSCNN_ERR_UNSUPPORTED;
     return FSCNN_OK;
 }
@@ -488,8 +489,8 @@ static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int 
         return FSCNN_ERR_UNSUPPORTED;
     const int in4 = x_layout == FSCNN_LAYOUT_N4, out4 = y_layout == FSCNN_LAYOUT_N4;
     if ((in4 && ((uintptr_t)x_dev & 15)) || (out4 && ((uintptr_t)y_dev & 15))) return FSCNN_ERR_UNSUPPORTED;
-    const long long n4 = ((long long)N + 3) / 4 * 4;
-    if ((in4 && !fits_int(n4 * C * H * W)) || (out4 && !fits_int(n4 * f->K * Ho * Wo)))
+    // (a group of four interleaved images is indexed with ints, the groups with 64-bit offsets)
+    if ((in4 && !fits_int(4LL * C * H * W)) || (out4 && !fits_int(4LL * f->K * Ho * Wo)))
         return FSCNN_ERR_UNSUPPORTED;
     if (pool && (Ho < 2 || Wo < 2)) return FSCNN_ERR_SHAPE;   // empty pooled output
     int v;

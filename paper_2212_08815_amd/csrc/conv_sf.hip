@@ -857,7 +857,8 @@ hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, in
     const int nbat = ((N << band_shift) + G::IMGS - 1) / G::IMGS;
     if (csplit < 1 || (G::POOL && csplit != 1)) return hipErrorInvalidValue;
     const long long nblk = (long long)p.NG * tiles_x * tiles_y * nbat * csplit;
-    if (nblk <= 0 || nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    // (a dispatch counts its work-items in 32 bits)
+    if (nblk <= 0 || nblk > 0x7fffffffLL || nblk * G::NT > 0xffffffffLL) return hipErrorInvalidValue;
     // the vector loads of the records address them with 32-bit byte offsets
     if (G::VREC && (p.nrec + kPlanSpare) * (long long)sizeof(Rec) >= 0x7ffffff0LL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(conv_sf_tiled_kernel<G>, dim3((unsigned)nblk), dim3(G::NT), G::LDS_BYTES, st,
@@ -1210,7 +1211,7 @@ hipError_t launch_conv_sf_direct(const int *rowptr, const uint32_t *idx, const f
                                  int relu, float *y, hipStream_t st)
 {
     const long long nblk = (long long)((Wo + 63) / 64) * ((Ho + 3) / 4) * N * K;
-    if (nblk <= 0 || nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (nblk <= 0 || nblk > 0x7fffffffLL || nblk * 256 > 0xffffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(conv_sf_direct_kernel, dim3((unsigned)nblk), dim3(256), 0, st, rowptr, idx,
                        val, x, N, C, H, W, K, R, S, Ho, Wo, sh, sw, ph, pw, bias, relu, y);
     return hipGetLastError();

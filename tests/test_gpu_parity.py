@@ -630,6 +630,44 @@ def test_largest_image_the_tiled_kernel_addresses(F, wd, tiled):
 
 
 # ------------------------------------------------------------------ YOLO-shaped stack (second workload)
+def test_batch_of_more_than_2_31_elements(F):
+    # 2100 images of 16 x 256 x 256: image 2048 starts exactly 2^31 floats into x and y.  Images
+    # are addressed with 64-bit offsets; the ones around the 32-bit boundaries and the last one are
+    # compared whole with the oracle, for NCHW and N4 tensors, plain and with the merged pool.
+    n, c, k, h = 2100, 16, 16, 256
+    assert n * c * h * h > 2 ** 31
+    _, w, b = inputs.random_layer(77, 1, c, k, 3, 3, 3, 3, 0.3)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1234)
+    x = torch.empty((n, c, h, h), device="cuda").uniform_(-1.0, 1.0, generator=g)
+    picks = [0, 1023, 1024, 2047, 2048, 2099]
+    xs = np.stack([host(x[i]) for i in picks])
+    csr = oracle.filter_compress(w)
+    o, a = oracle.conv2d_sparse_filter(xs, csr, w.shape, (1, 1), (1, 1), b, True, want_abs=True)
+    op = oracle.maxpool2x2(o)
+    ap = oracle.maxpool2x2(a.astype(np.float32)).astype(np.float64) * (1 + 1e-6)
+    f = F.filter_compress(dev(w))
+    x4 = x.view(n // 4, 4, c, h, h).permute(0, 2, 3, 4, 1).contiguous()
+    for xl, xin in ((F.NCHW, x), (F.N4, x4)):
+        for yl in (F.NCHW, F.N4):
+            for pool in (False, True):
+                y = F.conv2d_sparse_filter(f, xin, (1, 1), (1, 1), dev(b), True, x_layout=xl, y_layout=yl, n=n, pool=pool)
+                torch.cuda.synchronize()
+                if yl == F.NCHW:
+                    got = np.stack([host(y[i]) for i in picks])
+                else:
+                    got = np.stack([host(y[i // 4, ..., i % 4]) for i in picks])
+                assert_parity(got, op if pool else o, ap if pool else a, row_nmax(w),
+                              "large batch layouts %d->%d pool %d" % (xl, yl, pool))
+                del y
+    # the direct kernel (5x5 filters) as well
+    _, w5, b5 = inputs.random_layer(78, 1, c, 4, 5, 5, 5, 5, 0.2)
+    o5, a5 = oracle.conv2d_sparse_filter(xs, oracle.filter_compress(w5), w5.shape, (1, 1), (2, 2), b5, True, want_abs=True)
+    y = F.conv2d_sparse_filter(F.filter_compress(dev(w5)), x, (1, 1), (2, 2), dev(b5), True)
+    torch.cuda.synchronize()
+    assert_parity(np.stack([host(y[i]) for i in picks]), o5, a5, row_nmax(w5), "large batch, direct kernel")
+
+
 def test_yolo_shaped_stack_chain(F):
     """Darknet-53's 52 convolutions as a chain (3x3 stride 1 and 2, 1x1, LeakyReLU 0.1), reduced
     width and image size: every layer against the oracle on the GPU's own previous output, N4
