@@ -320,7 +320,8 @@ def test_conv_n4_layouts_match_oracle(F, case):
                                   (2, 512, 33, 7, 7, 0.05, False, True), (5, 96, 64, 28, 28, 0.10, True, True)])
 def test_small_problems_split_the_channel_range(F, case):
     """Few work-groups and many input channels: the automatic configuration splits the channel
-    chunks over several groups (atomic partial sums, then bias + ReLU in a finishing pass)."""
+    chunks over several groups (a copy of the partial sums per part, added up in the order of the
+    parts with bias + ReLU by a finishing pass; with one or two images the groups work on bands)."""
     n, c, k, h, w_, keep, use_b, relu = case
     x, w, b = inputs.random_layer(sum(case[:5]), n, c, k, h, w_, 3, 3, keep, bias=use_b)
     csr = oracle.filter_compress(w)
