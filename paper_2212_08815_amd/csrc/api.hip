@@ -520,7 +520,7 @@ static fscnn_status_t conv_sf_common(fscnn_filter_t *f, const float *x_dev, int 
                               &parts);
             if (s != FSCNN_OK) return s;
         }
-        int *cnt = (emit_cnt && csplit == 1 && !out4 && !pool && band_shift == 0) ? emit_cnt : nullptr;
+        int *cnt = (emit_cnt && csplit == 1 && !out4 && !pool) ? emit_cnt : nullptr;
         FSCNN_HIP(launch_conv_sf_tiled(*p, x_dev, N, C, H, W, f->K, Ho, Wo, ph, pw, bias_dev, relu,
                                        y_dev, in4, out4, pool, csplit, parts, cnt, band_shift, band_h, st));
         if (counted) *counted = cnt != nullptr;

@@ -739,9 +739,10 @@ conv_sf_tiled_kernel(const float *__restrict__ x, float *__restrict__ y,
                 const int plh = (G::LW == 16 && G::LHR == 4) ? (((plg & 1) << 1) | (plg >> 1)) : plg;
                 const int pig = ln / (G::LW * G::LHR);
                 const int v = p / G::BV, b = p % G::BV;
-                const int n = n0 + pig * G::BV + b, oy = ty0 + plh * G::NV + v, ox2 = tx0 + plx;
+                const int slot = n0 + pig * G::BV + b, ly = ty0 + plh * G::NV + v, ox2 = tx0 + plx;
+                const int n = slot >> bsh_out, oy = (slot & ((1 << bsh_out) - 1)) * band_h + ly;
                 const int step = kg * STEPS + st;
-                if (n < N && oy < Ho && ox2 < Wo && step < NCH8)
+                if (n < N && ly < band_h && oy < Ho && ox2 < Wo && step < NCH8)
                     emit_cnt[(((long long)n * Ho + oy) * Wo + ox2) * NCH8 + step] = c;
             }
         }
@@ -847,7 +848,7 @@ hipError_t launch_tiled(const SfPlan &p, const float *x, int N, int C, int H, in
     // band mode: the image slots of the launch are bands of band_h output rows (see the kernel)
     if (band_shift != 0) {
         if (G::IN4 || G::OUT4 || G::BV != 4 || band_shift < 0 || band_shift > 2 || band_h < 1 ||
-            (G::POOL && band_h % 2 != 0) || emit_cnt || ((long long)N << band_shift) > 0x7fffffffLL)
+            (G::POOL && band_h % 2 != 0) || ((long long)N << band_shift) > 0x7fffffffLL)
             return hipErrorInvalidValue;
     } else {
         band_h = Ho;
