@@ -220,6 +220,17 @@ def test_band_mode_for_one_or_two_images(F, n, h, w_, pad):
             ref = oracle.maxpool2x2(want) if pool else want
             assert np.array_equal(got, ref), "n %d %dx%d variant %d pool %d bands %d x %d rows" % (n, h, w_, v, pool, bands, rows)
     assert banded >= 8
+    # 3x3 at stride 2 and 1x1 filters through their own configurations, in bands as well
+    for r, stride, pd, extent in ((3, (2, 2), (1, 1), "3x3s2"), (1, (1, 1), (0, 0), "1x1")):
+        xs, ws, bs = inputs.random_layer(n * 77 + h + r, n, c, k, h, w_, r, r, 0.3, integer=True)
+        ref = oracle.conv2d_dense(xs, ws, stride, pd, bs, True)
+        fs = F.filter_compress(dev(ws))
+        for v in [0] + tiled_variants(F, extent=extent):
+            vv = v or F.sf_variant_choice(fs, n, h, w_, stride=stride)
+            if vv > 0:
+                assert F.sf_band_choice(vv, n, ref.shape[2])[0] == 4 // n
+            got = host(F.conv2d_sparse_filter(fs, dev(xs), stride, pd, dev(bs), True, variant=v))
+            assert np.array_equal(got, ref), "n %d %dx%d %s variant %d" % (n, h, w_, extent, v)
     assert F.sf_band_choice(F.sf_variant_choice(f, n, h, w_, n4=True), n, ho, n4=True) == (1, ho)   # N4 tensors: no bands
     assert F.sf_band_choice(F.sf_variant_choice(f, 3, h, w_), 3, ho) == (1, ho)                     # three images: none
 
